@@ -1,0 +1,135 @@
+/*
+ * libadt — Approximate Data Transfer (ADT) pack / unpack and the Adaptive
+ * Weight Precision (AWP) per-layer statistics of arXiv 2004.02297, for AMD
+ * MI355X (gfx950).  Plain C ABI: pointers and sizes only.
+ *
+ * Conventions common to all calls
+ *   - "device" pointers are HIP device memory of the CURRENT device; "host"
+ *     pointers are ordinary host memory.  The caller owns every buffer.
+ *   - The small per-layer tables (layer_offsets, bytes_per_layer) are HOST
+ *     arrays.  They are read during the call and may be changed or freed as
+ *     soon as it returns.
+ *   - layer_offsets has n_layers + 1 entries in ELEMENT units:
+ *     layer_offsets[0] == 0, non-decreasing, layer_offsets[n_layers] == N.
+ *     All layers' weights are contiguous in one FP32 buffer.  Empty layers
+ *     are legal.
+ *   - bytes_per_layer[l] in {1, 2, 3, 4} is the layer's "RoundTo".
+ *   - GPU work is enqueued on `stream` (a hipStream_t; NULL is the default
+ *     stream) and the call returns without waiting for it.
+ *   - Return value: ADT_OK (0) or a negative adt_status.  Arguments are
+ *     validated before anything is launched; on error nothing is written.
+ *     n_layers == 0 or N == 0 succeeds without a launch.
+ *   - No call throws or exits.  adt_strerror() gives a text for a status and
+ *     adt_last_error() the detail of the calling thread's last failure.
+ *
+ * Packed stream (wire format written by adt_pack, read by adt_unpack)
+ *   Layer l starts at byte P_l = sum_{j<l} n_j * r_j: the running byte offset
+ *   of Bitpack (Algorithm 2) carried across layers, no padding anywhere.
+ *   Weight i of layer l occupies bytes [P_l + i*r_l, P_l + (i+1)*r_l) and
+ *   holds the r_l most significant bytes of its 32-bit IEEE-754 word
+ *   (Section III: keeping N bits discards the 32-N lowest bits), least
+ *   significant kept byte first.  With r = 4 the stream is a copy of the
+ *   weights; with r = 2 it is an array of bfloat16 obtained by truncation.
+ *   The paper does not fix the byte order inside an element; this header does.
+ */
+#ifndef ADT_H_
+#define ADT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *adt_stream_t;
+
+enum adt_status {
+    ADT_OK = 0,
+    ADT_EINVAL = -1,  /* null pointer, n_layers < 0, byte count outside 1..4,
+                         offsets not starting at 0 or decreasing              */
+    ADT_EALIGN = -2,  /* a float buffer is not 4-byte aligned                  */
+    ADT_EHIP = -3,    /* HIP runtime / launch failure (see adt_last_error)     */
+    ADT_ENOMEM = -4,  /* the library's scratch memory could not be allocated   */
+    ADT_ERANGE = -5   /* sizes exceed what one launch can address              */
+};
+
+/* Number of statistics awp_layer_stats writes per layer, and their order. */
+#define AWP_NSTATS 3
+#define AWP_STAT_SUMSQ 0   /* sum of w^2                     */
+#define AWP_STAT_L2 1      /* sqrt of it: the l2-norm |W_l|  */
+#define AWP_STAT_ABSMAX 2  /* largest |w|                    */
+
+/*
+ * Size in bytes of the packed stream: sum over layers of n_l * r_l
+ * (Algorithm 2's final POffset).  Host only, no GPU.  Negative adt_status on
+ * an invalid table.
+ */
+int64_t adt_packed_size(const int64_t *layer_offsets /* host */,
+                        const uint8_t *bytes_per_layer /* host */,
+                        int n_layers);
+
+/*
+ * Bitpack (Section III-A, Algorithm 2) of all layers in one launch.
+ *   weights  device, N floats, 4-byte aligned (16-byte alignment is fastest)
+ *   out      device, at least adt_packed_size(...) bytes, any alignment; must
+ *            not overlap `weights`.  Bytes beyond the packed size are not
+ *            touched.
+ */
+int adt_pack(const float *weights, const int64_t *layer_offsets,
+             const uint8_t *bytes_per_layer, int n_layers, uint8_t *out,
+             adt_stream_t stream);
+
+/*
+ * Bitunpack (Section III-C, Algorithm 5) of all layers in one launch: every
+ * weight becomes its r stored bytes shifted left by 8*(4-r) bits, the low
+ * bits zero.  Hence unpack(pack(w)) == bits(w) & (0xFFFFFFFF << 8*(4-r)).
+ *   packed       device, stream written by adt_pack with the same two tables
+ *   weights_out  device, N floats, 4-byte aligned; must not overlap `packed`
+ */
+int adt_unpack(const uint8_t *packed, const int64_t *layer_offsets,
+               const uint8_t *bytes_per_layer, int n_layers,
+               float *weights_out, adt_stream_t stream);
+
+/*
+ * Per-layer statistics AWP monitors (Section II: the l2-norm of all weights
+ * of a layer, every batch, on the full-precision weights).
+ *   stats_out  device, n_layers * AWP_NSTATS doubles, row l =
+ *              { sum w^2, sqrt(sum w^2), max |w| }.  Squares and sums are
+ *              taken in double precision; partial sums are combined in a
+ *              fixed order, so results are identical from run to run.  An
+ *              empty layer gives {0, 0, 0}; a NaN weight makes all three NaN.
+ * Uses per-device scratch memory owned by the library (grown on demand, kept
+ * until adt_shutdown): concurrent calls on one device must share a stream.
+ */
+int awp_layer_stats(const float *weights, const int64_t *layer_offsets,
+                    int n_layers, double *stats_out, adt_stream_t stream);
+
+/*
+ * One batch of the AWP rule (Section II, Algorithm 1) for all layers.  Host
+ * only, no GPU; all pointers are host arrays of n_layers entries.
+ *   delta = (l2_now - l2_prev) / l2_prev; if delta < T the layer's counter
+ *   goes up by one; if the counter equals `interval` the layer gains `n_bits`
+ *   bits (capped at 32) and its counter returns to zero.  The counter is
+ *   cumulative (Algorithm 1 has no else-branch).  Then l2_prev := l2_now and
+ *   bytes_out[l] = ceil(bits[l] / 8) (Section III-A: 14 bits -> 2 bytes).
+ *   With is_first_batch != 0 only l2_prev and bytes_out are written.  A zero
+ *   previous norm gives delta = 0 if the norm is still zero, else +infinity.
+ */
+int awp_update(const double *l2_now, double *l2_prev, int32_t *counter,
+               int32_t *bits, uint8_t *bytes_out, int n_layers, double T,
+               int interval, int n_bits, int is_first_batch);
+
+/* Text for a status code (static string). */
+const char *adt_strerror(int status);
+
+/* Detail of the calling thread's most recent failure ("" if none). */
+const char *adt_last_error(void);
+
+/* Frees the library's per-device scratch memory.  Optional. */
+int adt_shutdown(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADT_H_ */

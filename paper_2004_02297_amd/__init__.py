@@ -1,0 +1,11 @@
+"""MI355X-native ADT pack / unpack and AWP layer statistics (arXiv 2004.02297).
+
+Thin Python binding over the C-ABI library ``libadt.so`` (see include/adt.h).
+PyTorch is used for device memory and streams only; every step of the method
+on the weights runs in the library's gfx950 kernels.  There is no CPU fallback:
+if the library is missing, loading fails.
+"""
+from .binding import (  # noqa: F401
+    AWP_NSTATS, AdtError, AwpState, adt_pack, adt_packed_size, adt_unpack,
+    awp_layer_stats, awp_update, lib_path, load_library,
+)

@@ -1,0 +1,188 @@
+"""ctypes binding of libadt.so: argument marshalling only.
+
+Function names and argument order follow include/adt.h.  Device buffers are
+torch CUDA(HIP) tensors; the per-layer tables are host numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+from . import _build
+
+AWP_NSTATS = 3
+_lib = None
+
+
+class AdtError(RuntimeError):
+    def __init__(self, status: int, text: str, detail: str):
+        super().__init__(f"libadt status {status} ({text}): {detail}")
+        self.status = status
+        self.detail = detail
+
+
+def lib_path() -> str:
+    return _build.LIB
+
+
+def load_library():
+    """Load the in-tree libadt.so; build it only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build_library()
+    lib = ctypes.CDLL(_build.LIB)
+    P, I, I64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    lib.adt_packed_size.restype = I64
+    lib.adt_packed_size.argtypes = [P, P, I]
+    lib.adt_pack.restype = I
+    lib.adt_pack.argtypes = [P, P, P, I, P, P]
+    lib.adt_unpack.restype = I
+    lib.adt_unpack.argtypes = [P, P, P, I, P, P]
+    lib.awp_layer_stats.restype = I
+    lib.awp_layer_stats.argtypes = [P, P, I, P, P]
+    lib.awp_update.restype = I
+    lib.awp_update.argtypes = [P, P, P, P, P, I, ctypes.c_double, I, I, I]
+    lib.adt_strerror.restype = ctypes.c_char_p
+    lib.adt_strerror.argtypes = [I]
+    lib.adt_last_error.restype = ctypes.c_char_p
+    lib.adt_last_error.argtypes = []
+    lib.adt_shutdown.restype = I
+    lib.adt_shutdown.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status < 0:
+        lib = load_library()
+        raise AdtError(status, lib.adt_strerror(status).decode(),
+                       lib.adt_last_error().decode())
+
+
+def _host(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _hptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _dev_tensor(t, dtype, name):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a device tensor")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous {dtype} tensor")
+    return t
+
+
+def adt_packed_size(layer_offsets, bytes_per_layer) -> int:
+    off = _host(layer_offsets, np.int64)
+    rb = _host(bytes_per_layer, np.uint8)
+    n = load_library().adt_packed_size(_hptr(off), _hptr(rb), off.size - 1)
+    _check(n)
+    return int(n)
+
+
+def adt_pack(weights, layer_offsets, bytes_per_layer, out=None, stream=None):
+    """adt_pack: device float32[N] -> device uint8[packed size]."""
+    import torch
+    off = _host(layer_offsets, np.int64)
+    rb = _host(bytes_per_layer, np.uint8)
+    L = off.size - 1
+    if rb.size != L:
+        raise ValueError("bytes_per_layer must have n_layers entries")
+    w = _dev_tensor(weights, torch.float32, "weights")
+    size = adt_packed_size(off, rb)
+    if w.numel() != int(off[-1]):
+        raise ValueError("weights size does not match layer_offsets[-1]")
+    if out is None:
+        out = torch.empty(size, dtype=torch.uint8, device=w.device)
+    else:
+        _dev_tensor(out, torch.uint8, "out")
+        if out.numel() < size:
+            raise ValueError("out is smaller than the packed size")
+    _check(load_library().adt_pack(w.data_ptr() or None, _hptr(off), _hptr(rb), L,
+                                   out.data_ptr() or None, _stream(stream)))
+    return out
+
+
+def adt_unpack(packed, layer_offsets, bytes_per_layer, out=None, stream=None):
+    """adt_unpack: device uint8 stream -> device float32[N]."""
+    import torch
+    off = _host(layer_offsets, np.int64)
+    rb = _host(bytes_per_layer, np.uint8)
+    L = off.size - 1
+    if rb.size != L:
+        raise ValueError("bytes_per_layer must have n_layers entries")
+    p = _dev_tensor(packed, torch.uint8, "packed")
+    if p.numel() < adt_packed_size(off, rb):
+        raise ValueError("packed is smaller than the packed size")
+    n = int(off[-1])
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=p.device)
+    else:
+        _dev_tensor(out, torch.float32, "out")
+        if out.numel() != n:
+            raise ValueError("out size does not match layer_offsets[-1]")
+    _check(load_library().adt_unpack(p.data_ptr() or None, _hptr(off), _hptr(rb), L,
+                                     out.data_ptr() or None, _stream(stream)))
+    return out
+
+
+def awp_layer_stats(weights, layer_offsets, out=None, stream=None):
+    """awp_layer_stats: device float32[N] -> device float64[L, 3]."""
+    import torch
+    off = _host(layer_offsets, np.int64)
+    L = off.size - 1
+    w = _dev_tensor(weights, torch.float32, "weights")
+    if w.numel() != int(off[-1]):
+        raise ValueError("weights size does not match layer_offsets[-1]")
+    if out is None:
+        out = torch.empty((L, AWP_NSTATS), dtype=torch.float64, device=w.device)
+    else:
+        _dev_tensor(out, torch.float64, "out")
+        if out.numel() != L * AWP_NSTATS:
+            raise ValueError("out must hold n_layers * 3 doubles")
+    _check(load_library().awp_layer_stats(w.data_ptr() or None, _hptr(off), L,
+                                          out.data_ptr() or None, _stream(stream)))
+    return out
+
+
+class AwpState:
+    """Host arrays the AWP rule carries from batch to batch."""
+
+    def __init__(self, n_layers: int, init_bits: int = 8):
+        self.n_layers = n_layers
+        self.bits = np.full(n_layers, init_bits, dtype=np.int32)
+        self.counter = np.zeros(n_layers, dtype=np.int32)
+        self.l2_prev = np.zeros(n_layers, dtype=np.float64)
+        self.bytes = np.zeros(n_layers, dtype=np.uint8)
+        self.first = True
+
+
+def awp_update(state: AwpState, l2_now, T: float, interval: int, n_bits: int = 8):
+    """awp_update: one batch of the rule on host arrays; returns bytes per layer."""
+    l2 = _host(l2_now, np.float64)
+    if l2.shape != (state.n_layers,):
+        raise ValueError("l2_now must have n_layers entries")
+    _check(load_library().awp_update(_hptr(l2), _hptr(state.l2_prev), _hptr(state.counter),
+                                     _hptr(state.bits), _hptr(state.bytes), state.n_layers,
+                                     float(T), int(interval), int(n_bits),
+                                     1 if state.first else 0))
+    state.first = False
+    return state.bytes.copy()

@@ -1,0 +1,377 @@
+// C-ABI entry points of libadt (declared in include/adt.h): argument
+// validation, per-layer table construction, scratch management, launches.
+// All arithmetic of the method on weights happens in the gfx950 kernels; the
+// only host arithmetic is on the n_layers-sized tables and the scalar AWP rule.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/adt.h"
+#include "adt_tables.h"
+
+namespace adt {
+hipError_t launch_pack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
+                       hipStream_t stream);
+hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
+                         hipStream_t stream);
+hipError_t launch_stats(const StatsArgs &a, const StatsFinalArgs &f, uint32_t n_tiles,
+                        bool inline_table, hipStream_t stream);
+}  // namespace adt
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int status, const std::string &detail) {
+    g_err = detail;
+    return status;
+}
+
+int fail_hip(hipError_t e, const char *what) {
+    return fail(ADT_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+// ---- per-device state -----------------------------------------------------
+// Large tables (more than adt::kInlineLayers layers) are staged through a
+// small ring: pinned host buffer -> device buffer, with an event per slot so
+// that a slot is not rewritten while a kernel may still read it.
+struct Slot {
+    void *host = nullptr;
+    void *dev = nullptr;
+    size_t cap = 0;
+    hipEvent_t ev = nullptr;
+    bool pending = false;
+};
+
+struct DeviceState {
+    Slot ring[4];
+    int next = 0;
+    void *stats_scratch = nullptr;
+    size_t stats_cap = 0;
+};
+
+std::mutex g_mu;
+std::map<int, DeviceState> g_state;
+
+void release_slot(Slot &s) {
+    if (s.pending && s.ev) (void)hipEventSynchronize(s.ev);
+    if (s.dev) (void)hipFree(s.dev);
+    if (s.host) (void)hipHostFree(s.host);
+    if (s.ev) (void)hipEventDestroy(s.ev);
+    s = Slot();
+}
+
+int acquire_slot(DeviceState &st, size_t bytes, Slot **out) {
+    Slot &s = st.ring[st.next];
+    st.next = (st.next + 1) % 4;
+    if (s.pending) {
+        hipError_t e = hipEventSynchronize(s.ev);
+        if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize");
+        s.pending = false;
+    }
+    if (!s.ev) {
+        hipError_t e = hipEventCreateWithFlags(&s.ev, hipEventDisableTiming);
+        if (e != hipSuccess) return fail_hip(e, "hipEventCreate");
+    }
+    if (s.cap < bytes) {
+        if (s.dev) (void)hipFree(s.dev);
+        if (s.host) (void)hipHostFree(s.host);
+        s.dev = s.host = nullptr;
+        s.cap = 0;
+        size_t cap = bytes * 2;
+        if (hipMalloc(&s.dev, cap) != hipSuccess) {
+            (void)hipGetLastError();
+            s.dev = nullptr;
+            return fail(ADT_ENOMEM, "device table buffer");
+        }
+        if (hipHostMalloc(&s.host, cap, hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            (void)hipFree(s.dev);
+            s.dev = s.host = nullptr;
+            return fail(ADT_ENOMEM, "pinned table buffer");
+        }
+        s.cap = cap;
+    }
+    *out = &s;
+    return ADT_OK;
+}
+
+size_t align8(size_t x) { return (x + 7) & ~(size_t)7; }
+
+// ---- validation -------------------------------------------------------------
+int check_tables(const int64_t *off, const uint8_t *rb, bool need_rb, int n_layers) {
+    if (n_layers < 0) return fail(ADT_EINVAL, "n_layers < 0");
+    if (!off) return fail(ADT_EINVAL, "layer_offsets is null");
+    if (off[0] != 0) return fail(ADT_EINVAL, "layer_offsets[0] != 0");
+    if (need_rb && n_layers > 0 && !rb) return fail(ADT_EINVAL, "bytes_per_layer is null");
+    for (int l = 0; l < n_layers; ++l) {
+        if (off[l + 1] < off[l])
+            return fail(ADT_EINVAL, "layer_offsets decreases at layer " + std::to_string(l));
+        if (need_rb && (rb[l] < 1 || rb[l] > 4))
+            return fail(ADT_EINVAL, "bytes_per_layer[" + std::to_string(l) + "] not in 1..4");
+    }
+    return ADT_OK;
+}
+
+// Tiles per layer -> exclusive prefix; fails if one launch cannot hold them.
+int build_tile_off(const int64_t *off, int n_layers, int64_t tile, uint32_t *tile_off) {
+    int64_t t = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        tile_off[l] = (uint32_t)t;
+        t += (off[l + 1] - off[l] + tile - 1) / tile;
+        if (t >= ((int64_t)1 << 31)) return fail(ADT_ERANGE, "too many tiles for one launch");
+    }
+    tile_off[n_layers] = (uint32_t)t;
+    return ADT_OK;
+}
+
+enum Direction { kPack, kUnpack };
+
+int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
+                   const uint8_t *rb, int n_layers, const void *packed, adt_stream_t stream) {
+    int rc = check_tables(off, rb, true, n_layers);
+    if (rc) return rc;
+    const int64_t n = n_layers ? off[n_layers] : 0;
+    if (n_layers == 0 || n == 0) return ADT_OK;
+    if (!weights || !packed) return fail(ADT_EINVAL, "null device pointer");
+    if ((uintptr_t)weights & 3u) return fail(ADT_EALIGN, "FP32 buffer is not 4-byte aligned");
+
+    adt::PackArgs a;
+    a.weights = (const uint32_t *)weights;
+    a.packed = (uint8_t *)packed;
+    a.n_layers = n_layers;
+    a.dev = adt::DeviceTable{nullptr, nullptr, nullptr, nullptr};
+    const bool inl = n_layers <= adt::kInlineLayers;
+    hipStream_t hs = (hipStream_t)stream;
+
+    std::unique_lock<std::mutex> lock(g_mu, std::defer_lock);
+    Slot *slot = nullptr;
+    int64_t *elem_off, *pack_off;
+    uint32_t *tile_off;
+    uint8_t *rbytes;
+    size_t bytes = 0;
+    if (inl) {
+        elem_off = a.inl.elem_off;
+        pack_off = a.inl.pack_off;
+        tile_off = a.inl.tile_off;
+        rbytes = a.inl.rbytes;
+    } else {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+        const size_t L1 = (size_t)n_layers + 1;
+        const size_t o_pack = align8(8 * L1), o_tile = o_pack + align8(8 * L1);
+        const size_t o_rb = o_tile + align8(4 * L1);
+        bytes = o_rb + align8((size_t)n_layers);
+        lock.lock();
+        rc = acquire_slot(g_state[dev], bytes, &slot);
+        if (rc) return rc;
+        char *h = (char *)slot->host, *d = (char *)slot->dev;
+        elem_off = (int64_t *)h;
+        pack_off = (int64_t *)(h + o_pack);
+        tile_off = (uint32_t *)(h + o_tile);
+        rbytes = (uint8_t *)(h + o_rb);
+        a.dev = adt::DeviceTable{(const int64_t *)d, (const int64_t *)(d + o_pack),
+                                 (const uint32_t *)(d + o_tile), (const uint8_t *)(d + o_rb)};
+    }
+
+    int64_t p = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        elem_off[l] = off[l];
+        pack_off[l] = p;
+        rbytes[l] = rb[l];
+        p += (off[l + 1] - off[l]) * (int64_t)rb[l];
+    }
+    elem_off[n_layers] = off[n_layers];
+    pack_off[n_layers] = p;
+    a.packed_size = p;
+    rc = build_tile_off(off, n_layers, adt::kBlockTile, tile_off);
+    if (rc) return rc;
+    const uint32_t n_tiles = tile_off[n_layers];
+
+    if (!inl) {
+        hipError_t e = hipMemcpyAsync(slot->dev, slot->host, bytes, hipMemcpyHostToDevice, hs);
+        if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(table)");
+    }
+    hipError_t e = dir == kPack ? adt::launch_pack(a, n_tiles, inl, hs)
+                                : adt::launch_unpack(a, n_tiles, inl, hs);
+    if (!inl) {
+        // guard the slot even if the launch failed: the copy may be in flight
+        if (hipEventRecord(slot->ev, hs) == hipSuccess) slot->pending = true;
+        else (void)hipStreamSynchronize(hs);
+    }
+    if (e != hipSuccess) return fail_hip(e, dir == kPack ? "pack launch" : "unpack launch");
+    return ADT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t adt_packed_size(const int64_t *layer_offsets, const uint8_t *bytes_per_layer,
+                        int n_layers) {
+    int rc = check_tables(layer_offsets, bytes_per_layer, true, n_layers);
+    if (rc) return rc;
+    int64_t p = 0;
+    for (int l = 0; l < n_layers; ++l)
+        p += (layer_offsets[l + 1] - layer_offsets[l]) * (int64_t)bytes_per_layer[l];
+    return p;
+}
+
+int adt_pack(const float *weights, const int64_t *layer_offsets,
+             const uint8_t *bytes_per_layer, int n_layers, uint8_t *out,
+             adt_stream_t stream) {
+    return pack_or_unpack(kPack, weights, layer_offsets, bytes_per_layer, n_layers, out, stream);
+}
+
+int adt_unpack(const uint8_t *packed, const int64_t *layer_offsets,
+               const uint8_t *bytes_per_layer, int n_layers, float *weights_out,
+               adt_stream_t stream) {
+    return pack_or_unpack(kUnpack, weights_out, layer_offsets, bytes_per_layer, n_layers,
+                          packed, stream);
+}
+
+int awp_layer_stats(const float *weights, const int64_t *layer_offsets, int n_layers,
+                    double *stats_out, adt_stream_t stream) {
+    int rc = check_tables(layer_offsets, nullptr, false, n_layers);
+    if (rc) return rc;
+    if (n_layers == 0) return ADT_OK;
+    const int64_t n = layer_offsets[n_layers];
+    if (!stats_out) return fail(ADT_EINVAL, "stats_out is null");
+    if (n > 0 && !weights) return fail(ADT_EINVAL, "weights is null");
+    if ((uintptr_t)weights & 3u) return fail(ADT_EALIGN, "FP32 buffer is not 4-byte aligned");
+    if ((uintptr_t)stats_out & 7u) return fail(ADT_EALIGN, "stats_out is not 8-byte aligned");
+
+    hipStream_t hs = (hipStream_t)stream;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+
+    adt::StatsArgs a;
+    adt::StatsFinalArgs f;
+    const bool inl = n_layers <= adt::kInlineLayers;
+    const size_t L1 = (size_t)n_layers + 1;
+    const size_t o_tile = align8(8 * L1);
+    const size_t bytes = o_tile + align8(4 * L1);
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState &st = g_state[dev];
+    Slot *slot = nullptr;
+    int64_t *elem_off;
+    uint32_t *tile_off;
+    a.dev_elem_off = nullptr;
+    a.dev_tile_off = nullptr;
+    f.dev_tile_off = nullptr;
+    if (inl) {
+        elem_off = a.inl.elem_off;
+        tile_off = a.inl.tile_off;
+    } else {
+        rc = acquire_slot(st, bytes, &slot);
+        if (rc) return rc;
+        elem_off = (int64_t *)slot->host;
+        tile_off = (uint32_t *)((char *)slot->host + o_tile);
+        a.dev_elem_off = (const int64_t *)slot->dev;
+        a.dev_tile_off = (const uint32_t *)((char *)slot->dev + o_tile);
+        f.dev_tile_off = a.dev_tile_off;
+    }
+    for (int l = 0; l <= n_layers; ++l) elem_off[l] = layer_offsets[l];
+    rc = build_tile_off(layer_offsets, n_layers, adt::kStatsTile, tile_off);
+    if (rc) return rc;
+    const uint32_t n_tiles = tile_off[n_layers];
+    if (inl) memcpy(f.inl_tile_off, tile_off, 4 * L1);
+
+    // scratch: n_tiles doubles, then n_tiles magnitude words
+    const size_t need = (size_t)n_tiles * 12 + 16;
+    if (st.stats_cap < need) {
+        if (st.stats_scratch) (void)hipFree(st.stats_scratch);   // waits for the device
+        st.stats_scratch = nullptr;
+        st.stats_cap = 0;
+        const size_t cap = need + need / 2 + 4096;
+        if (hipMalloc(&st.stats_scratch, cap) != hipSuccess) {
+            (void)hipGetLastError();
+            st.stats_scratch = nullptr;
+            return fail(ADT_ENOMEM, "statistics scratch");
+        }
+        st.stats_cap = cap;
+    }
+    a.weights = (const uint32_t *)weights;
+    a.partial_sumsq = (double *)st.stats_scratch;
+    a.partial_absmax = (uint32_t *)((char *)st.stats_scratch + align8((size_t)n_tiles * 8));
+    a.n_layers = n_layers;
+    f.partial_sumsq = a.partial_sumsq;
+    f.partial_absmax = a.partial_absmax;
+    f.stats_out = stats_out;
+    f.n_layers = n_layers;
+
+    if (!inl) {
+        e = hipMemcpyAsync(slot->dev, slot->host, bytes, hipMemcpyHostToDevice, hs);
+        if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(table)");
+    }
+    e = adt::launch_stats(a, f, n_tiles, inl, hs);
+    if (!inl) {
+        if (hipEventRecord(slot->ev, hs) == hipSuccess) slot->pending = true;
+        else (void)hipStreamSynchronize(hs);
+    }
+    if (e != hipSuccess) return fail_hip(e, "statistics launch");
+    return ADT_OK;
+}
+
+int awp_update(const double *l2_now, double *l2_prev, int32_t *counter, int32_t *bits,
+               uint8_t *bytes_out, int n_layers, double T, int interval, int n_bits,
+               int is_first_batch) {
+    if (n_layers < 0) return fail(ADT_EINVAL, "n_layers < 0");
+    if (n_layers > 0 && (!l2_now || !l2_prev || !counter || !bits || !bytes_out))
+        return fail(ADT_EINVAL, "null state array");
+    for (int l = 0; l < n_layers; ++l) {
+        if (!is_first_batch) {
+            const double prev = l2_prev[l], now = l2_now[l];
+            const double delta = prev == 0.0 ? (now == 0.0 ? 0.0 : (double)INFINITY)
+                                             : (now - prev) / prev;
+            if (delta < T) ++counter[l];
+            if (counter[l] == interval) {
+                const int32_t b = bits[l] + n_bits;
+                bits[l] = b > 32 ? 32 : b;
+                counter[l] = 0;
+            }
+        }
+        l2_prev[l] = l2_now[l];
+        bytes_out[l] = (uint8_t)((bits[l] + 7) >> 3);
+    }
+    return ADT_OK;
+}
+
+const char *adt_strerror(int status) {
+    switch (status) {
+        case ADT_OK: return "success";
+        case ADT_EINVAL: return "invalid argument";
+        case ADT_EALIGN: return "misaligned buffer";
+        case ADT_EHIP: return "HIP runtime error";
+        case ADT_ENOMEM: return "out of memory";
+        case ADT_ERANGE: return "size out of range";
+        default: return "unknown status";
+    }
+}
+
+const char *adt_last_error(void) { return g_err.c_str(); }
+
+int adt_shutdown(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    int saved = 0;
+    const bool have = hipGetDevice(&saved) == hipSuccess;
+    for (auto &kv : g_state) {
+        if (hipSetDevice(kv.first) != hipSuccess) continue;
+        for (Slot &s : kv.second.ring) release_slot(s);
+        if (kv.second.stats_scratch) (void)hipFree(kv.second.stats_scratch);
+    }
+    g_state.clear();
+    if (have) (void)hipSetDevice(saved);
+    return ADT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,356 @@
+// ADT Bitpack / Bitunpack for gfx950 (Section III, Algorithms 2 and 5 of
+// arXiv 2004.02297), all layers in one launch.
+//
+// Work decomposition.  A wavefront owns a "wave tile" of 1024 consecutive
+// weights of one layer; four wave tiles make a block tile.  A wave moves its
+// tile in three steps and never talks to another wave, so no block barrier is
+// needed:
+//   pack   : 4 coalesced 128-bit loads per lane of FP32 words
+//            -> keep the top r bytes of every word in registers
+//            -> write the r-byte stream to the wave's LDS slice
+//            -> read it back as 16-byte pieces in stream order
+//            -> 128-bit stores on 16-byte aligned addresses of the stream.
+//   unpack : the mirror image (aligned 128-bit loads of the stream -> LDS ->
+//            r(+1) dwords per 4 weights -> shift each weight's bytes to the
+//            top of a zeroed word -> 128-bit stores of FP32).
+// The stream side is always accessed on the 16-byte grid of absolute
+// addresses, whatever the layer's start offset is: a misaligned tile reads
+// its LDS slice at a shifted position (funnel shift by the byte phase) and
+// only the first and last piece of a tile fall back to byte accesses.
+// The FP32 side needs 4-byte alignment only; the hardware splits a 128-bit
+// access that is not 16-byte aligned.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "adt_tables.h"
+
+namespace adt {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));   // FP32 side: dword aligned
+
+constexpr int kPadDw = 8;                              // LDS pad before / after
+constexpr int kWaveLdsDw = kPadDw + kWaveTile + kPadDw;  // 1040 dwords per wave
+constexpr int kPadBytes = kPadDw * 4;
+
+__device__ __forceinline__ void wave_lds_sync() {
+    // LDS traffic of one wave is served in order; this only stops the
+    // compiler from moving accesses across the exchange point.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ({hi,lo} >> 8*sh) truncated to 32 bits, sh in 0..3.
+__device__ __forceinline__ uint32_t funnel(uint32_t hi, uint32_t lo, uint32_t sh) {
+    return (uint32_t)((((uint64_t)hi << 32) | lo) >> (8u * sh));
+}
+
+// Top R bytes of four words, as R dwords of stream (low kept byte first).
+template <int R>
+__device__ __forceinline__ void keep_top_bytes(const u32x4 u, uint32_t *d) {
+    if (R == 4) {
+        d[0] = u.x; d[1] = u.y; d[2] = u.z; d[3] = u.w;
+    } else if (R == 3) {
+        d[0] = (u.x >> 8) | ((u.y >> 8) << 24);
+        d[1] = (u.y >> 16) | ((u.z >> 8) << 16);
+        d[2] = (u.z >> 24) | ((u.w >> 8) << 8);
+    } else if (R == 2) {
+        d[0] = (u.x >> 16) | (u.y & 0xFFFF0000u);
+        d[1] = (u.z >> 16) | (u.w & 0xFFFF0000u);
+    } else {
+        d[0] = (u.x >> 24) | ((u.y >> 24) << 8) | ((u.z >> 24) << 16) |
+               (u.w & 0xFF000000u);
+    }
+}
+
+// Inverse: R dwords of stream -> four words with the low 8*(4-R) bits zero.
+template <int R>
+__device__ __forceinline__ u32x4 shift_to_top(const uint32_t *y) {
+    u32x4 u;
+    if (R == 4) {
+        u.x = y[0]; u.y = y[1]; u.z = y[2]; u.w = y[3];
+    } else if (R == 3) {
+        u.x = y[0] << 8;
+        u.y = ((y[0] >> 24) | (y[1] << 8)) << 8;
+        u.z = ((y[1] >> 16) | (y[2] << 16)) << 8;
+        u.w = y[2] & 0xFFFFFF00u;
+    } else if (R == 2) {
+        u.x = y[0] << 16;
+        u.y = y[0] & 0xFFFF0000u;
+        u.z = y[1] << 16;
+        u.w = y[1] & 0xFFFF0000u;
+    } else {
+        u.x = y[0] << 24;
+        u.y = (y[0] << 16) & 0xFF000000u;
+        u.z = (y[0] << 8) & 0xFF000000u;
+        u.w = y[0] & 0xFF000000u;
+    }
+    return u;
+}
+
+__device__ __forceinline__ uint32_t byte_of(const u32x4 v, int t) {
+    uint32_t w = (t < 8) ? ((t < 4) ? v.x : v.y) : ((t < 12) ? v.z : v.w);
+    return (w >> (8 * (t & 3))) & 0xFFu;
+}
+
+// ---------------------------------------------------------------------------
+// Pack one wave tile: `len` (1..1024) FP32 words at src -> len*R bytes at dst.
+// lds: this wave's slice (kWaveLdsDw dwords).
+// ---------------------------------------------------------------------------
+template <int R>
+__device__ __forceinline__ void pack_wave_tile(const uint32_t *__restrict__ src,
+                                               uint8_t *__restrict__ dst, int len,
+                                               uint32_t *lds, int lane) {
+    uint32_t *body = lds + kPadDw;
+    const uint32_t s = (uint32_t)((uintptr_t)dst & 15u);   // wave uniform
+    const bool full = (len == kWaveTile);
+
+    if (full) {
+        u32x4 v[kChunksPerLane];
+#pragma unroll
+        for (int j = 0; j < kChunksPerLane; ++j)
+            v[j] = *(const u32x4_a4 *)(src + 4 * (j * kWave + lane));
+#pragma unroll
+        for (int j = 0; j < kChunksPerLane; ++j) {
+            uint32_t d[4];
+            keep_top_bytes<R>(v[j], d);
+            uint32_t *p = body + (j * kWave + lane) * R;
+#pragma unroll
+            for (int t = 0; t < R; ++t) p[t] = d[t];
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kChunksPerLane; ++j) {
+            const int c = j * kWave + lane;
+            const int e0 = 4 * c;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (e0 + 4 <= len) {
+                v = *(const u32x4_a4 *)(src + e0);
+            } else {
+                if (e0 < len) v.x = src[e0];
+                if (e0 + 1 < len) v.y = src[e0 + 1];
+                if (e0 + 2 < len) v.z = src[e0 + 2];
+            }
+            uint32_t d[4];
+            keep_top_bytes<R>(v, d);
+            uint32_t *p = body + c * R;
+#pragma unroll
+            for (int t = 0; t < R; ++t) p[t] = d[t];
+        }
+    }
+    wave_lds_sync();
+
+    if (full && s == 0) {
+        // stream side 16-byte aligned: R full-width stores per lane
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            const int q = k * kWave + lane;
+            const u32x4 o = *(const u32x4 *)(body + 4 * q);
+            *(u32x4 *)(dst + 16 * q) = o;
+        }
+        return;
+    }
+
+    // General case: walk the 16-byte grid of absolute stream addresses.
+    // Piece q covers tile-local stream bytes [16q - s, 16q - s + 16).
+    const int nbytes = len * R;
+    uint8_t *dst_al = dst - s;
+    const int npieces = (int)(s + nbytes + 15) >> 4;
+    const uint32_t sh = (0u - s) & 3u;
+    for (int k = 0; k * kWave < npieces; ++k) {
+        const int q = k * kWave + lane;
+        if (q < npieces) {
+            const int b0 = 16 * q - (int)s;
+            const int dw = (kPadBytes + b0) >> 2;          // >= 4, <= 1031
+            const uint32_t x0 = lds[dw], x1 = lds[dw + 1], x2 = lds[dw + 2],
+                           x3 = lds[dw + 3], x4 = lds[dw + 4];
+            u32x4 o;
+            o.x = funnel(x1, x0, sh);
+            o.y = funnel(x2, x1, sh);
+            o.z = funnel(x3, x2, sh);
+            o.w = funnel(x4, x3, sh);
+            if (b0 >= 0 && b0 + 16 <= nbytes) {
+                *(u32x4 *)(dst_al + 16 * q) = o;
+            } else {
+                for (int t = 0; t < 16; ++t) {
+                    const int bt = b0 + t;
+                    if (bt >= 0 && bt < nbytes) dst_al[16 * q + t] = (uint8_t)byte_of(o, t);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Unpack one wave tile: len*R stream bytes at src -> `len` FP32 words at dst.
+// [buf_lo, buf_hi) is the whole packed buffer: a 16-byte piece inside it may
+// be read whole even where it reaches into a neighbouring tile.
+// ---------------------------------------------------------------------------
+template <int R>
+__device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src,
+                                                 uint32_t *__restrict__ dst, int len,
+                                                 const uint8_t *buf_lo,
+                                                 const uint8_t *buf_hi, uint32_t *lds,
+                                                 int lane) {
+    const uint32_t s = (uint32_t)((uintptr_t)src & 15u);   // wave uniform
+    const bool full = (len == kWaveTile);
+
+    if (full && s == 0) {
+        u32x4 v[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k)
+            v[k] = *(const u32x4 *)(src + 16 * (k * kWave + lane));
+#pragma unroll
+        for (int k = 0; k < R; ++k) *(u32x4 *)(lds + 4 * (k * kWave + lane)) = v[k];
+        wave_lds_sync();
+#pragma unroll
+        for (int j = 0; j < kChunksPerLane; ++j) {
+            const int c = j * kWave + lane;
+            uint32_t y[4];
+#pragma unroll
+            for (int t = 0; t < R; ++t) y[t] = lds[c * R + t];
+            *(u32x4_a4 *)(dst + 4 * c) = shift_to_top<R>(y);
+        }
+        return;
+    }
+
+    const int nbytes = len * R;
+    const uint8_t *src_al = src - s;
+    const int npieces = (int)(s + nbytes + 15) >> 4;       // <= 257
+    for (int k = 0; k * kWave < npieces; ++k) {
+        const int q = k * kWave + lane;
+        if (q < npieces) {
+            const uint8_t *a = src_al + 16 * q;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (a >= buf_lo && a + 16 <= buf_hi) {
+                v = *(const u32x4 *)a;
+            } else {
+                uint32_t w[4] = {0u, 0u, 0u, 0u};
+                for (int t = 0; t < 16; ++t)
+                    if (a + t >= buf_lo && a + t < buf_hi)
+                        w[t >> 2] |= (uint32_t)a[t] << (8 * (t & 3));
+                v.x = w[0]; v.y = w[1]; v.z = w[2]; v.w = w[3];
+            }
+            *(u32x4 *)(lds + 4 * q) = v;
+        }
+    }
+    wave_lds_sync();
+
+    // Stream byte b of the tile sits at LDS byte b + s.
+    const uint32_t sh = s & 3u;
+#pragma unroll
+    for (int j = 0; j < kChunksPerLane; ++j) {
+        const int c = j * kWave + lane;
+        const int e0 = 4 * c;
+        if (e0 < len) {
+            const int d = (int)(s + 4 * c * R) >> 2;        // <= 1023
+            uint32_t x[5];
+#pragma unroll
+            for (int t = 0; t <= R; ++t) x[t] = lds[d + t];
+            uint32_t y[4];
+#pragma unroll
+            for (int t = 0; t < R; ++t) y[t] = funnel(x[t + 1], x[t], sh);
+            const u32x4 u = shift_to_top<R>(y);
+            if (e0 + 4 <= len) {
+                *(u32x4_a4 *)(dst + e0) = u;
+            } else {
+                dst[e0] = u.x;
+                if (e0 + 1 < len) dst[e0 + 1] = u.y;
+                if (e0 + 2 < len) dst[e0 + 2] = u.z;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Kernels: block -> (layer, tile) through the offset table, wave -> wave tile.
+// ---------------------------------------------------------------------------
+struct TileRef {
+    int64_t elem;      // first weight of the wave tile (absolute index)
+    int64_t byte;      // first stream byte of the wave tile
+    int len;           // weights in the wave tile, 0 = nothing to do
+    int r;
+};
+
+template <bool INLINE>
+__device__ __forceinline__ TileRef locate(const PackArgs &a, uint32_t block, int wave) {
+    const uint32_t *tile_off = INLINE ? a.inl.tile_off : a.dev.tile_off;
+    const int64_t *elem_off = INLINE ? a.inl.elem_off : a.dev.elem_off;
+    const int64_t *pack_off = INLINE ? a.inl.pack_off : a.dev.pack_off;
+    const uint8_t *rbytes = INLINE ? a.inl.rbytes : a.dev.rbytes;
+    int lo = 0, hi = a.n_layers;            // largest lo with tile_off[lo] <= block
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tile_off[mid] <= block) lo = mid; else hi = mid;
+    }
+    const int64_t e_begin = elem_off[lo];
+    const int64_t n = elem_off[lo + 1] - e_begin;
+    const int64_t first = (int64_t)(block - tile_off[lo]) * kBlockTile +
+                          (int64_t)wave * kWaveTile;
+    TileRef t;
+    t.r = rbytes[lo];
+    t.elem = e_begin + first;
+    t.byte = pack_off[lo] + first * t.r;
+    const int64_t left = n - first;
+    t.len = left <= 0 ? 0 : (left < kWaveTile ? (int)left : kWaveTile);
+    return t;
+}
+
+template <bool INLINE>
+__global__ __launch_bounds__(kBlock) void pack_kernel(const PackArgs a) {
+    __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    const TileRef t = locate<INLINE>(a, blockIdx.x, wave);
+    if (t.len == 0) return;
+    const uint32_t *src = a.weights + t.elem;
+    uint8_t *dst = a.packed + t.byte;
+    uint32_t *lds = smem[wave];
+    switch (t.r) {
+        case 1: pack_wave_tile<1>(src, dst, t.len, lds, lane); break;
+        case 2: pack_wave_tile<2>(src, dst, t.len, lds, lane); break;
+        case 3: pack_wave_tile<3>(src, dst, t.len, lds, lane); break;
+        default: pack_wave_tile<4>(src, dst, t.len, lds, lane); break;
+    }
+}
+
+template <bool INLINE>
+__global__ __launch_bounds__(kBlock) void unpack_kernel(const PackArgs a) {
+    __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    const TileRef t = locate<INLINE>(a, blockIdx.x, wave);
+    if (t.len == 0) return;
+    const uint8_t *src = a.packed + t.byte;
+    uint32_t *dst = const_cast<uint32_t *>(a.weights) + t.elem;
+    const uint8_t *lo = a.packed;
+    const uint8_t *hi = a.packed + a.packed_size;
+    uint32_t *lds = smem[wave];
+    switch (t.r) {
+        case 1: unpack_wave_tile<1>(src, dst, t.len, lo, hi, lds, lane); break;
+        case 2: unpack_wave_tile<2>(src, dst, t.len, lo, hi, lds, lane); break;
+        case 3: unpack_wave_tile<3>(src, dst, t.len, lo, hi, lds, lane); break;
+        default: unpack_wave_tile<4>(src, dst, t.len, lo, hi, lds, lane); break;
+    }
+}
+
+hipError_t launch_pack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
+                       hipStream_t stream) {
+    if (inline_table)
+        pack_kernel<true><<<dim3(n_tiles), dim3(kBlock), 0, stream>>>(a);
+    else
+        pack_kernel<false><<<dim3(n_tiles), dim3(kBlock), 0, stream>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
+                         hipStream_t stream) {
+    if (inline_table)
+        unpack_kernel<true><<<dim3(n_tiles), dim3(kBlock), 0, stream>>>(a);
+    else
+        unpack_kernel<false><<<dim3(n_tiles), dim3(kBlock), 0, stream>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace adt

@@ -1,0 +1,76 @@
+// Per-layer tables shared by the host launcher and the gfx950 kernels.
+//
+// One launch covers all layers: the grid is the concatenation of every
+// layer's tiles, and a block finds its layer by a binary search over
+// tile_off.  Tables of up to ADT_INLINE_LAYERS layers travel inside the
+// kernel-argument buffer (no copy, no lifetime to manage); larger ones are
+// staged through a ring of device buffers.
+#pragma once
+
+#include <stdint.h>
+
+namespace adt {
+
+constexpr int kWave = 64;               // CDNA wavefront
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWave * kWavesPerBlock;
+constexpr int kChunksPerLane = 4;       // 128-bit loads in flight per lane
+constexpr int kWaveTile = kWave * kChunksPerLane * 4;    // 1024 weights per wave
+constexpr int kBlockTile = kWaveTile * kWavesPerBlock;   // 4096 weights per block
+
+// Statistics kernel: 16 128-bit loads per lane, 16384 weights per block.
+constexpr int kStatsLoadsPerLane = 16;
+constexpr int kStatsTile = kBlock * kStatsLoadsPerLane * 4;
+
+constexpr int kInlineLayers = 128;
+
+// Layer l covers weights [elem_off[l], elem_off[l+1]), packed bytes
+// [pack_off[l], pack_off[l+1]) and tiles [tile_off[l], tile_off[l+1]).
+struct InlineTable {
+    int64_t elem_off[kInlineLayers + 1];
+    int64_t pack_off[kInlineLayers + 1];
+    uint32_t tile_off[kInlineLayers + 1];
+    uint8_t rbytes[kInlineLayers];
+};
+
+struct DeviceTable {
+    const int64_t *elem_off;
+    const int64_t *pack_off;
+    const uint32_t *tile_off;
+    const uint8_t *rbytes;
+};
+
+struct PackArgs {
+    const uint32_t *weights;   // FP32 words, read by pack / written by unpack
+    uint8_t *packed;           // dense stream
+    int64_t packed_size;       // bytes in the whole stream
+    int n_layers;
+    DeviceTable dev;           // used when n_layers > kInlineLayers
+    InlineTable inl;
+};
+
+struct StatsInlineTable {
+    int64_t elem_off[kInlineLayers + 1];
+    uint32_t tile_off[kInlineLayers + 1];
+};
+
+struct StatsArgs {
+    const uint32_t *weights;
+    double *partial_sumsq;     // one per tile
+    uint32_t *partial_absmax;  // one per tile, magnitude bits
+    int n_layers;
+    const int64_t *dev_elem_off;
+    const uint32_t *dev_tile_off;
+    StatsInlineTable inl;
+};
+
+struct StatsFinalArgs {
+    const double *partial_sumsq;
+    const uint32_t *partial_absmax;
+    double *stats_out;         // n_layers x 3
+    int n_layers;
+    const uint32_t *dev_tile_off;
+    uint32_t inl_tile_off[kInlineLayers + 1];
+};
+
+}  // namespace adt

@@ -1,0 +1,166 @@
+// Per-layer statistics of AWP for gfx950 (Section II of arXiv 2004.02297:
+// the l2-norm of all weights of a layer, taken every batch).
+//
+// Two launches for all layers together:
+//   1. partial kernel: the grid is the concatenation of every layer's tiles
+//      of 16384 weights.  A lane issues 128-bit loads, squares in double
+//      precision (the square of a binary32 value is exact in binary64) and
+//      keeps four running sums; a wave combines its lanes with xor-shuffles,
+//      the block combines its four waves through LDS, and one partial
+//      {sum of squares, largest magnitude} per tile goes to scratch memory.
+//   2. final kernel: one block per layer adds that layer's partials in a fixed
+//      order and writes {sum, sqrt(sum), max |w|}.
+// No atomics: the order of every addition is fixed by the indices alone, so
+// the result is bit-identical from run to run.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "adt_tables.h"
+
+namespace adt {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;   // every lane holds the same value
+}
+
+__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)v, off, kWave);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// Magnitude bits: ordering them as unsigned integers orders finite values and
+// infinity by magnitude and puts every NaN above infinity, so a NaN wins.
+__device__ __forceinline__ void accumulate(uint32_t bits, double &acc, uint32_t &mag) {
+    const double w = (double)__uint_as_float(bits);
+    acc = fma(w, w, acc);
+    const uint32_t m = bits & 0x7FFFFFFFu;
+    mag = m > mag ? m : mag;
+}
+
+__device__ __forceinline__ void block_combine(double sum, uint32_t mag, double *out_sum,
+                                              uint32_t *out_mag) {
+    __shared__ double wsum[kWavesPerBlock];
+    __shared__ uint32_t wmag[kWavesPerBlock];
+    sum = wave_sum(sum);
+    mag = wave_max(mag);
+    const int wave = (int)(threadIdx.x >> 6);
+    if ((threadIdx.x & 63) == 0) {
+        wsum[wave] = sum;
+        wmag[wave] = mag;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        *out_sum = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+        uint32_t m = wmag[0];
+#pragma unroll
+        for (int i = 1; i < kWavesPerBlock; ++i) m = wmag[i] > m ? wmag[i] : m;
+        *out_mag = m;
+    }
+}
+
+template <bool INLINE>
+__global__ __launch_bounds__(kBlock) void stats_partial_kernel(const StatsArgs a) {
+    const uint32_t *tile_off = INLINE ? a.inl.tile_off : a.dev_tile_off;
+    const int64_t *elem_off = INLINE ? a.inl.elem_off : a.dev_elem_off;
+    const uint32_t block = blockIdx.x;
+    int lo = 0, hi = a.n_layers;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tile_off[mid] <= block) lo = mid; else hi = mid;
+    }
+    const int64_t e_begin = elem_off[lo];
+    const int64_t first = (int64_t)(block - tile_off[lo]) * kStatsTile;
+    const int64_t left = (elem_off[lo + 1] - e_begin) - first;   // > 0 by construction
+    const int len = left < kStatsTile ? (int)left : kStatsTile;
+    const uint32_t *src = a.weights + e_begin + first;
+    const int tid = (int)threadIdx.x;
+
+    double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+    uint32_t mag = 0u;
+    if (len == kStatsTile) {
+#pragma unroll
+        for (int it = 0; it < kStatsLoadsPerLane / 4; ++it) {
+            u32x4 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                v[j] = *(const u32x4_a4 *)(src + 4 * ((it * 4 + j) * kBlock + tid));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                accumulate(v[j].x, acc0, mag);
+                accumulate(v[j].y, acc1, mag);
+                accumulate(v[j].z, acc2, mag);
+                accumulate(v[j].w, acc3, mag);
+            }
+        }
+    } else {
+        for (int i = 0; i < kStatsLoadsPerLane; ++i) {
+            const int e0 = 4 * (i * kBlock + tid);
+            if (e0 + 4 <= len) {
+                const u32x4 v = *(const u32x4_a4 *)(src + e0);
+                accumulate(v.x, acc0, mag);
+                accumulate(v.y, acc1, mag);
+                accumulate(v.z, acc2, mag);
+                accumulate(v.w, acc3, mag);
+            } else {
+                if (e0 < len) accumulate(src[e0], acc0, mag);
+                if (e0 + 1 < len) accumulate(src[e0 + 1], acc1, mag);
+                if (e0 + 2 < len) accumulate(src[e0 + 2], acc2, mag);
+            }
+        }
+    }
+    block_combine((acc0 + acc1) + (acc2 + acc3), mag, &a.partial_sumsq[block],
+                  &a.partial_absmax[block]);
+}
+
+template <bool INLINE>
+__global__ __launch_bounds__(kBlock) void stats_final_kernel(const StatsFinalArgs a) {
+    const uint32_t *tile_off = INLINE ? a.inl_tile_off : a.dev_tile_off;
+    const int layer = (int)blockIdx.x;
+    const uint32_t begin = tile_off[layer], end = tile_off[layer + 1];
+    double acc = 0.0;
+    uint32_t mag = 0u;
+    for (uint32_t i = begin + threadIdx.x; i < end; i += kBlock) {
+        acc += a.partial_sumsq[i];
+        const uint32_t m = a.partial_absmax[i];
+        mag = m > mag ? m : mag;
+    }
+    __shared__ double tot_sum;
+    __shared__ uint32_t tot_mag;
+    block_combine(acc, mag, &tot_sum, &tot_mag);
+    if (threadIdx.x == 0) {
+        double *o = a.stats_out + (int64_t)layer * 3;
+        const double absmax = (double)__uint_as_float(tot_mag);
+        // a NaN weight poisons the sum as well; keep the three outputs consistent
+        o[0] = tot_sum;
+        o[1] = sqrt(tot_sum);
+        o[2] = absmax;
+    }
+}
+
+hipError_t launch_stats(const StatsArgs &a, const StatsFinalArgs &f, uint32_t n_tiles,
+                        bool inline_table, hipStream_t stream) {
+    if (n_tiles > 0) {
+        if (inline_table)
+            stats_partial_kernel<true><<<dim3(n_tiles), dim3(kBlock), 0, stream>>>(a);
+        else
+            stats_partial_kernel<false><<<dim3(n_tiles), dim3(kBlock), 0, stream>>>(a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (inline_table)
+        stats_final_kernel<true><<<dim3(f.n_layers), dim3(kBlock), 0, stream>>>(f);
+    else
+        stats_final_kernel<false><<<dim3(f.n_layers), dim3(kBlock), 0, stream>>>(f);
+    return hipGetLastError();
+}
+
+}  // namespace adt

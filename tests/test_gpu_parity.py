@@ -1,0 +1,251 @@
+"""GPU parity: libadt (through its C ABI) against the CPU oracle, bit for bit.
+
+Pack streams and unpacked words must be identical to the oracle's; statistics
+must agree to 1e-5 relative (the stated bar) and are checked to 1e-10: both
+sides add exact double-precision squares, in different orders; the oracle's
+index-order sum of n terms carries a rounding error of about sqrt(n) * 2^-53
+(1e-12 at n = 1e8), the kernels' tree-shaped sum less.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+STATS_RTOL_BAR = 1e-5      # the required tolerance
+STATS_RTOL = 1e-10         # what the kernels are expected to reach
+MASK = {1: 0xFF000000, 2: 0xFFFF0000, 3: 0xFFFFFF00, 4: 0xFFFFFFFF}
+
+
+@pytest.fixture(scope="module")
+def adt():
+    import paper_2004_02297_amd as m
+    m.load_library()
+    return m
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_pack_unpack(adt, w, off, rb, w_shift=0, p_shift=0):
+    """Pack + unpack on the GPU with guard bytes around both outputs and the
+    given misalignment of the base pointers (w_shift in elements, p_shift in
+    bytes); compare with the oracle."""
+    n = int(off[-1])
+    size = oracle.packed_size(off, rb)
+    exp_stream = oracle.pack(w, off, rb)
+    exp_back = oracle.unpack(exp_stream, off, rb)
+
+    guard = 64
+    wbuf = torch.zeros(n + w_shift + 8, dtype=torch.float32, device="cuda")
+    wview = wbuf[w_shift:w_shift + n]
+    wview.copy_(torch.from_numpy(w))
+    pbuf = torch.full((size + p_shift + 2 * guard,), 0xA5, dtype=torch.uint8, device="cuda")
+    pview = pbuf[guard + p_shift:guard + p_shift + size]
+    adt.adt_pack(wview, off, rb, out=pview)
+    got = pbuf.cpu().numpy()
+    lo, hi = guard + p_shift, guard + p_shift + size
+    assert np.all(got[:lo] == 0xA5) and np.all(got[hi:] == 0xA5), "pack wrote outside its stream"
+    assert np.array_equal(got[lo:hi], exp_stream), "packed stream differs from the oracle"
+
+    obuf = torch.full((n + w_shift + 2 * guard,), float("nan"), dtype=torch.float32, device="cuda")
+    obuf.view(torch.int32).fill_(0x5A5A5A5A)
+    oview = obuf[guard + w_shift:guard + w_shift + n]
+    adt.adt_unpack(pview, off, rb, out=oview)
+    gotw = obuf.view(torch.int32).cpu().numpy().view(np.uint32)
+    lo, hi = guard + w_shift, guard + w_shift + n
+    assert np.all(gotw[:lo] == 0x5A5A5A5A) and np.all(gotw[hi:] == 0x5A5A5A5A), \
+        "unpack wrote outside its output"
+    assert np.array_equal(gotw[lo:hi], exp_back.view(np.uint32)), "unpacked words differ"
+    # what is unique: the closed form the oracle is pinned to
+    u = w.view(np.uint32)
+    for l in range(len(rb)):
+        seg = slice(int(off[l]), int(off[l + 1]))
+        assert np.array_equal(gotw[lo:hi][seg], u[seg] & np.uint32(MASK[int(rb[l])]))
+
+
+def check_stats(adt, w, off, rtol=STATS_RTOL):
+    exp = oracle.stats(w, off)
+    got = adt.awp_layer_stats(dev(w), off).cpu().numpy()
+    assert got.shape == exp.shape
+    assert STATS_RTOL <= STATS_RTOL_BAR
+    nan = np.isnan(exp)
+    assert np.array_equal(np.isnan(got), nan)
+    np.testing.assert_allclose(got[~nan], exp[~nan], rtol=rtol, atol=0.0)
+    np.testing.assert_array_equal(got[:, 2][~nan[:, 2]], exp[:, 2][~nan[:, 2]])   # absmax exact
+    return got
+
+
+# ------------------------------------------------------------------ configs
+def test_tiny_config(adt):
+    ws = workloads.make_weight_set("tiny")
+    rb = workloads.config_bytes("tiny")
+    assert adt.adt_packed_size(ws.layer_offsets, rb) == 35168
+    check_pack_unpack(adt, ws.weights, ws.layer_offsets, rb)
+    check_stats(adt, ws.weights, ws.layer_offsets)
+
+
+@pytest.mark.parametrize("name,variant", [
+    ("alexnet", "default"), ("resnet50", "default"),
+    ("vgg16", "all2"), ("vgg16", "all3"), ("vgg16", "mixed"),
+])
+def test_full_size_configs(adt, name, variant):
+    ws = workloads.make_weight_set(name)
+    rb = workloads.config_bytes(name, variant)
+    off, w = ws.layer_offsets, ws.weights
+    exp_stream = oracle.pack(w, off, rb)
+    dw = dev(w)
+    packed = adt.adt_pack(dw, off, rb)
+    assert packed.numel() == exp_stream.size
+    assert np.array_equal(packed.cpu().numpy(), exp_stream)
+    back = adt.adt_unpack(packed, off, rb)
+    exp_back = oracle.unpack(exp_stream, off, rb)
+    assert np.array_equal(back.view(torch.int32).cpu().numpy(), exp_back.view(np.int32))
+    del packed, back
+    if variant in ("default", "all2"):
+        check_stats(adt, w, off)
+
+
+def test_alexnet_hundred_passes_stay_identical(adt):
+    ws = workloads.make_weight_set("alexnet")
+    rb = workloads.config_bytes("alexnet")
+    off = ws.layer_offsets
+    dw = dev(ws.weights)
+    first_p = adt.adt_pack(dw, off, rb)
+    first_w = adt.adt_unpack(first_p, off, rb)
+    p = torch.empty_like(first_p)
+    w2 = torch.empty_like(first_w)
+    for _ in range(100):
+        adt.adt_pack(dw, off, rb, out=p)
+        adt.adt_unpack(p, off, rb, out=w2)
+    assert torch.equal(p, first_p)
+    assert torch.equal(w2.view(torch.int32), first_w.view(torch.int32))
+    assert np.array_equal(first_p.cpu().numpy(), oracle.pack(ws.weights, off, rb))
+
+
+# ------------------------------------------------------------------ ragged / edge cases
+@pytest.mark.parametrize("w_shift,p_shift", [(0, 0), (1, 0), (0, 1), (3, 7), (2, 13), (1, 15)])
+def test_alignment_sweep(adt, w_shift, p_shift):
+    off, rb, w = workloads.alignment_sweep_case()
+    check_pack_unpack(adt, w, off, rb, w_shift, p_shift)
+
+
+@pytest.mark.parametrize("r", [1, 2, 3, 4])
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 63, 64, 65, 1023, 1024, 1025, 4095, 4096, 4097,
+                               8192 + 17, 3 * 4096])
+def test_single_layer_sizes(adt, n, r):
+    off, rb, w = workloads.ragged_case([n], [r], seed=100 + n)
+    for p_shift in (0, 5):
+        check_pack_unpack(adt, w, off, rb, 0, p_shift)
+
+
+def test_special_values(adt):
+    w = np.tile(workloads.special_values(), 40)
+    for r in (1, 2, 3, 4):
+        off, rb, _ = workloads.ragged_case([w.size], [r], seed=0)
+        check_pack_unpack(adt, w, off, rb)
+
+
+def test_empty_inputs(adt):
+    z = torch.zeros(0, dtype=torch.float32, device="cuda")
+    off = np.array([0], dtype=np.int64)
+    assert adt.adt_pack(z, off, np.zeros(0, np.uint8)).numel() == 0
+    off = np.array([0, 0, 0], dtype=np.int64)
+    rb = np.array([1, 3], dtype=np.uint8)
+    p = adt.adt_pack(z, off, rb)
+    assert p.numel() == 0
+    assert adt.adt_unpack(p, off, rb).numel() == 0
+    st = adt.awp_layer_stats(z, off).cpu().numpy()
+    assert st.tolist() == [[0.0, 0.0, 0.0], [0.0, 0.0, 0.0]]
+
+
+def test_many_layers_use_the_device_table(adt):
+    rng = np.random.default_rng(77)
+    sizes = rng.integers(0, 9000, size=300)
+    sizes[::17] = 0
+    rb = rng.integers(1, 5, size=300).astype(np.uint8)
+    off, rb, w = workloads.ragged_case(sizes, rb, seed=78)
+    for _ in range(6):     # more calls than ring slots
+        check_pack_unpack(adt, w, off, rb, 1, 3)
+    off2, _, w2 = workloads.ragged_case(sizes, rb, seed=79, he=True)
+    for _ in range(6):
+        check_stats(adt, w2, off2)
+
+
+# ------------------------------------------------------------------ exhaustive bit patterns
+def test_all_bit_patterns_on_gpu(adt):
+    """Every 32-bit word, every byte count: unpack(pack(w)) equals the mask
+    closed form (checked on the device), and one slice is compared with the
+    oracle element by element."""
+    chunk = 1 << 28
+    off = np.array([0, chunk], dtype=np.int64)
+    for r in (1, 2, 3, 4):
+        rb = np.array([r], dtype=np.uint8)
+        mask = MASK[r] - (1 << 32)            # as a signed 32-bit value
+        p = torch.empty(chunk * r, dtype=torch.uint8, device="cuda")
+        back = torch.empty(chunk, dtype=torch.float32, device="cuda")
+        for c in range(16):
+            words = torch.arange(c * chunk - (1 << 31), (c + 1) * chunk - (1 << 31),
+                                 dtype=torch.int64, device="cuda").to(torch.int32)
+            adt.adt_pack(words.view(torch.float32), off, rb, out=p)
+            adt.adt_unpack(p, off, rb, out=back)
+            assert torch.equal(back.view(torch.int32), words & mask), (r, c)
+            if c == 5:
+                n = 1 << 22
+                hw = words[:n].cpu().numpy().view(np.float32)
+                o1 = np.array([0, n], dtype=np.int64)
+                assert np.array_equal(p[:n * r].cpu().numpy(), oracle.pack(hw, o1, rb))
+            del words
+
+
+# ------------------------------------------------------------------ statistics
+def test_stats_ragged_and_special(adt):
+    sizes = [0, 1, 2, 3, 5, 255, 256, 257, 16383, 16384, 16385, 0, 40000, 7]
+    off, _, w = workloads.ragged_case(sizes, [1] * len(sizes), seed=5, he=True)
+    check_stats(adt, w, off)
+    w2 = w.copy()
+    w2[int(off[4])] = np.nan          # layer 4 gets a NaN
+    w2[int(off[8]) + 9] = np.inf      # layer 8 an infinity
+    w2[int(off[12]) + 123] = -3e38    # layer 12 a huge value (no float32 overflow allowed)
+    got = check_stats(adt, w2, off)
+    assert np.isnan(got[4]).all() and got[8, 1] == np.inf and np.isfinite(got[12]).all()
+
+
+def test_stats_misaligned_base_and_determinism(adt):
+    ws = workloads.make_weight_set("resnet50")
+    off = ws.layer_offsets
+    buf = torch.zeros(ws.n_weights + 4, dtype=torch.float32, device="cuda")
+    exp = oracle.stats(ws.weights, off)
+    outs = []
+    for shift in (0, 1, 3):
+        v = buf[shift:shift + ws.n_weights]
+        v.copy_(torch.from_numpy(ws.weights))
+        outs.append(adt.awp_layer_stats(v, off).cpu().numpy())
+        np.testing.assert_allclose(outs[-1], exp, rtol=STATS_RTOL)
+    again = adt.awp_layer_stats(buf[3:3 + ws.n_weights], off).cpu().numpy()
+    assert again.tobytes() == outs[-1].tobytes()       # run-to-run identical
+    assert outs[0].tobytes() == outs[1].tobytes()      # independent of base alignment
+
+
+# ------------------------------------------------------------------ streams
+def test_non_default_stream(adt):
+    ws = workloads.make_weight_set("tiny")
+    rb = workloads.config_bytes("tiny")
+    dw = dev(ws.weights)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        p = adt.adt_pack(dw, ws.layer_offsets, rb)
+        b = adt.adt_unpack(p, ws.layer_offsets, rb)
+        st = adt.awp_layer_stats(dw, ws.layer_offsets)
+    s.synchronize()
+    exp = oracle.pack(ws.weights, ws.layer_offsets, rb)
+    assert np.array_equal(p.cpu().numpy(), exp)
+    assert np.array_equal(b.view(torch.int32).cpu().numpy(),
+                          oracle.unpack(exp, ws.layer_offsets, rb).view(np.int32))
+    np.testing.assert_allclose(st.cpu().numpy(), oracle.stats(ws.weights, ws.layer_offsets),
+                               rtol=STATS_RTOL)

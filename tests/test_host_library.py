@@ -1,0 +1,122 @@
+"""Host-side checks of libadt that need no GPU: the library loads, exports every
+symbol include/adt.h declares, rejects bad arguments before touching the GPU,
+and its scalar AWP rule agrees with the oracle's."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def adt():
+    import paper_2004_02297_amd as m
+    m.load_library()
+    return m
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "adt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:adt|awp)_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(adt):
+    syms = declared_symbols()
+    assert {"adt_pack", "adt_unpack", "awp_layer_stats", "adt_packed_size", "awp_update",
+            "adt_strerror", "adt_last_error", "adt_shutdown"} <= set(syms)
+    lib = ctypes.CDLL(adt.lib_path())
+    for s in syms:
+        assert hasattr(lib, s), f"{s} declared in adt.h but not exported"
+
+
+def test_packed_size(adt):
+    for name in ("tiny", "alexnet", "resnet50", "vgg16"):
+        shapes = workloads.SHAPES[name]()
+        off = workloads.offsets_from_sizes(workloads.layer_sizes(shapes))
+        rb = workloads.config_bytes(name)
+        assert adt.adt_packed_size(off, rb) == oracle.packed_size(off, rb)
+    assert adt.adt_packed_size(np.array([0, 8]), np.array([3], np.uint8)) == 24   # Figure 2
+    assert adt.adt_packed_size(np.array([0]), np.zeros(0, np.uint8)) == 0
+
+
+def test_config_sizes():
+    n = {k: int(workloads.layer_sizes(f()).sum()) for k, f in workloads.SHAPES.items()}
+    assert n == {"tiny": 10160, "alexnet": 61090496, "resnet50": 25502912, "vgg16": 138344128}
+    assert len(workloads.resnet50_shapes()) == 54
+
+
+def test_invalid_arguments_fail_before_any_launch(adt):
+    lib = adt.load_library()
+    off = np.array([0, 4, 8], dtype=np.int64)
+    rb = np.array([2, 3], dtype=np.uint8)
+    fake = ctypes.c_void_p(0x1000)      # never dereferenced: validation comes first
+
+    def ptr(a):
+        return a.ctypes.data_as(ctypes.c_void_p)
+
+    EINVAL, EALIGN = -1, -2
+    bad_r = np.array([2, 5], dtype=np.uint8)
+    zero_r = np.array([0, 1], dtype=np.uint8)
+    dec = np.array([0, 9, 8], dtype=np.int64)
+    nz = np.array([1, 4, 8], dtype=np.int64)
+    for fn in (lib.adt_pack, lib.adt_unpack):
+        assert fn(fake, ptr(off), ptr(bad_r), 2, fake, None) == EINVAL
+        assert fn(fake, ptr(off), ptr(zero_r), 2, fake, None) == EINVAL
+        assert fn(fake, ptr(dec), ptr(rb), 2, fake, None) == EINVAL
+        assert fn(fake, ptr(nz), ptr(rb), 2, fake, None) == EINVAL
+        assert fn(fake, None, ptr(rb), 2, fake, None) == EINVAL
+        assert fn(fake, ptr(off), None, 2, fake, None) == EINVAL
+        assert fn(fake, ptr(off), ptr(rb), -1, fake, None) == EINVAL
+        assert fn(None, ptr(off), ptr(rb), 2, fake, None) == EINVAL
+        assert fn(fake, ptr(off), ptr(rb), 2, None, None) == EINVAL
+        assert b"" != lib.adt_last_error()
+    assert lib.adt_pack(ctypes.c_void_p(0x1002), ptr(off), ptr(rb), 2, fake, None) == EALIGN
+    assert lib.adt_unpack(fake, ptr(off), ptr(rb), 2, ctypes.c_void_p(0x1001), None) == EALIGN
+    assert lib.awp_layer_stats(fake, ptr(dec), 2, fake, None) == EINVAL
+    assert lib.awp_layer_stats(fake, ptr(off), 2, None, None) == EINVAL
+    assert lib.awp_layer_stats(ctypes.c_void_p(0x1002), ptr(off), 2, fake, None) == EALIGN
+    assert lib.adt_packed_size(ptr(off), ptr(bad_r), 2) == EINVAL
+    # empty work succeeds without a GPU
+    e = np.array([0, 0, 0], dtype=np.int64)
+    assert lib.adt_pack(None, ptr(e), ptr(rb), 2, None, None) == 0
+    assert lib.adt_unpack(None, ptr(e), ptr(rb), 2, None, None) == 0
+    assert lib.adt_pack(None, ptr(e), None, 0, None, None) == 0
+    assert lib.adt_strerror(EINVAL) == b"invalid argument"
+    with pytest.raises(adt.AdtError):
+        adt.adt_packed_size(off, bad_r)
+
+
+def test_awp_update_matches_oracle_on_random_norm_sequences(adt):
+    rng = np.random.default_rng(42)
+    for trial in range(40):
+        L = int(rng.integers(1, 12))
+        T = float(rng.choice([-5e-2, -2e-3, -2e-5, 0.0, 1e-3, 0.5]))
+        interval = int(rng.integers(1, 6))
+        n_bits = int(rng.choice([8, 8, 6, 3, 16]))
+        init = int(rng.choice([8, 8, 1, 14, 16, 32]))
+        a = adt.AwpState(L, init)
+        o = oracle.AwpState(L, init)
+        norms = np.abs(rng.standard_normal(L)) + 0.1
+        norms[rng.random(L) < 0.15] = 0.0
+        for step in range(60):
+            ba = adt.awp_update(a, norms, T, interval, n_bits)
+            bo = oracle.awp_update(o, norms, T, interval, n_bits)
+            assert np.array_equal(ba, bo), (trial, step)
+            assert np.array_equal(a.bits, o.bits) and np.array_equal(a.counter, o.counter)
+            assert np.array_equal(a.l2_prev, o.l2_prev)
+            scale = 1.0 + rng.choice([-0.1, -1e-3, -1e-5, 0.0, 1e-5, 1e-3, 0.1], size=L)
+            norms = norms * scale
+            norms[rng.random(L) < 0.02] = 0.0
+            norms[(norms == 0.0) & (rng.random(L) < 0.3)] = 1.0
+
+
+def test_awp_update_paper_example_bytes(adt):
+    st = adt.AwpState(4, init_bits=14)
+    assert adt.awp_update(st, np.ones(4), -2e-3, 4000).tolist() == [2, 2, 2, 2]
