@@ -126,6 +126,24 @@ const char *adt_strerror(int status);
 /* Detail of the calling thread's most recent failure ("" if none). */
 const char *adt_last_error(void);
 
+/*
+ * Launch timing (measurement aid, off by default).  While enabled, every
+ * kernel the library launches carries the dispatch's own begin / end
+ * timestamps.  adt_timing_read waits for the launches recorded so far, writes
+ * per-kernel totals to `out` (host, ADT_NKERNELS entries, indexed as
+ * adt_kernel_name names them) and forgets them.
+ */
+#define ADT_NKERNELS 4
+typedef struct adt_kernel_time {
+    int64_t launches;
+    double total_ms;
+    double min_ms;
+    double max_ms;
+} adt_kernel_time;
+int adt_timing_enable(int on);
+int adt_timing_read(adt_kernel_time *out);
+const char *adt_kernel_name(int kernel);   /* "" outside 0..ADT_NKERNELS-1 */
+
 /* Frees the library's per-device scratch memory.  Optional. */
 int adt_shutdown(void);
 

@@ -14,7 +14,13 @@ import numpy as np
 from . import _build
 
 AWP_NSTATS = 3
+ADT_NKERNELS = 4
 _lib = None
+
+
+class _KernelTime(ctypes.Structure):
+    _fields_ = [("launches", ctypes.c_int64), ("total_ms", ctypes.c_double),
+                ("min_ms", ctypes.c_double), ("max_ms", ctypes.c_double)]
 
 
 class AdtError(RuntimeError):
@@ -51,6 +57,12 @@ def load_library():
     lib.adt_strerror.argtypes = [I]
     lib.adt_last_error.restype = ctypes.c_char_p
     lib.adt_last_error.argtypes = []
+    lib.adt_timing_enable.restype = I
+    lib.adt_timing_enable.argtypes = [I]
+    lib.adt_timing_read.restype = I
+    lib.adt_timing_read.argtypes = [P]
+    lib.adt_kernel_name.restype = ctypes.c_char_p
+    lib.adt_kernel_name.argtypes = [I]
     lib.adt_shutdown.restype = I
     lib.adt_shutdown.argtypes = []
     _lib = lib
@@ -186,3 +198,18 @@ def awp_update(state: AwpState, l2_now, T: float, interval: int, n_bits: int = 8
                                      1 if state.first else 0))
     state.first = False
     return state.bytes.copy()
+
+
+def adt_timing_enable(on: bool) -> None:
+    """adt_timing_enable: exact per-launch kernel durations on / off."""
+    _check(load_library().adt_timing_enable(1 if on else 0))
+
+
+def adt_timing_read() -> dict:
+    """adt_timing_read: {kernel name: {launches, total_ms, min_ms, max_ms}}."""
+    lib = load_library()
+    arr = (_KernelTime * ADT_NKERNELS)()
+    _check(lib.adt_timing_read(ctypes.cast(arr, ctypes.c_void_p)))
+    return {lib.adt_kernel_name(k).decode(): {
+        "launches": int(arr[k].launches), "total_ms": arr[k].total_ms,
+        "min_ms": arr[k].min_ms, "max_ms": arr[k].max_ms} for k in range(ADT_NKERNELS)}

@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "../../include/adt.h"
+#include "adt_launch.h"
 #include "adt_tables.h"
 
 namespace adt {
@@ -23,6 +24,8 @@ hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
 hipError_t launch_stats(const StatsArgs &a, const StatsFinalArgs &f, uint32_t n_tiles,
                         bool inline_table, hipStream_t stream);
 }  // namespace adt
+
+static_assert(ADT_NKERNELS == adt::kNumKernels, "adt.h and adt_launch.h disagree");
 
 namespace {
 
@@ -58,6 +61,16 @@ struct DeviceState {
 
 std::mutex g_mu;
 std::map<int, DeviceState> g_state;
+
+// ---- launch timing ----------------------------------------------------------
+struct TimedLaunch {
+    int kernel;
+    hipEvent_t start, stop;
+};
+std::mutex g_timing_mu;
+bool g_timing_on = false;
+std::vector<TimedLaunch> g_timed;                       // launches not yet read
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_spare;  // event pairs to reuse
 
 void release_slot(Slot &s) {
     if (s.pending && s.ev) (void)hipEventSynchronize(s.ev);
@@ -212,6 +225,24 @@ int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
 
 }  // namespace
 
+bool adt::timing_events(int kernel_id, hipEvent_t *start, hipEvent_t *stop) {
+    std::lock_guard<std::mutex> lock(g_timing_mu);
+    if (!g_timing_on) return false;
+    std::pair<hipEvent_t, hipEvent_t> ev{nullptr, nullptr};
+    if (!g_spare.empty()) {
+        ev = g_spare.back();
+        g_spare.pop_back();
+    } else if (hipEventCreate(&ev.first) != hipSuccess ||
+               hipEventCreate(&ev.second) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    g_timed.push_back(TimedLaunch{kernel_id, ev.first, ev.second});
+    *start = ev.first;
+    *stop = ev.second;
+    return true;
+}
+
 extern "C" {
 
 int64_t adt_packed_size(const int64_t *layer_offsets, const uint8_t *bytes_per_layer,
@@ -359,6 +390,46 @@ const char *adt_strerror(int status) {
 }
 
 const char *adt_last_error(void) { return g_err.c_str(); }
+
+int adt_timing_enable(int on) {
+    std::lock_guard<std::mutex> lock(g_timing_mu);
+    g_timing_on = on != 0;
+    return ADT_OK;
+}
+
+int adt_timing_read(adt_kernel_time *out) {
+    if (!out) return fail(ADT_EINVAL, "out is null");
+    std::lock_guard<std::mutex> lock(g_timing_mu);
+    for (int k = 0; k < ADT_NKERNELS; ++k) out[k] = adt_kernel_time{0, 0.0, 0.0, 0.0};
+    int rc = ADT_OK;
+    for (const TimedLaunch &t : g_timed) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(t.stop);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, t.start, t.stop);
+        if (e != hipSuccess) {
+            rc = fail_hip(e, "launch timing");
+        } else if (t.kernel >= 0 && t.kernel < ADT_NKERNELS) {
+            adt_kernel_time &o = out[t.kernel];
+            o.min_ms = o.launches == 0 || ms < o.min_ms ? ms : o.min_ms;
+            o.max_ms = ms > o.max_ms ? ms : o.max_ms;
+            o.total_ms += ms;
+            ++o.launches;
+        }
+        g_spare.emplace_back(t.start, t.stop);
+    }
+    g_timed.clear();
+    return rc;
+}
+
+const char *adt_kernel_name(int kernel) {
+    switch (kernel) {
+        case adt::kKernelPack: return "pack_kernel";
+        case adt::kKernelUnpack: return "unpack_kernel";
+        case adt::kKernelStatsPartial: return "stats_partial_kernel";
+        case adt::kKernelStatsFinal: return "stats_final_kernel";
+        default: return "";
+    }
+}
 
 int adt_shutdown(void) {
     std::lock_guard<std::mutex> lock(g_mu);

@@ -1,0 +1,38 @@
+// Kernel launch helper shared by the launchers: an ordinary launch, or, while
+// launch timing is switched on (adt_timing_enable), a launch bracketed by the
+// dispatch's own begin / end timestamps (hipExtLaunchKernel events), so that a
+// benchmark reads exact kernel durations without a profiler attached.
+#pragma once
+
+#include <hip/hip_ext.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "adt_tables.h"
+
+namespace adt {
+
+enum KernelId {
+    kKernelPack = 0,
+    kKernelUnpack = 1,
+    kKernelStatsPartial = 2,
+    kKernelStatsFinal = 3,
+    kNumKernels = 4
+};
+
+// Defined in adt_api.hip.  True (and a fresh event pair, owned by the timing
+// registry) when launch timing is on.
+bool timing_events(int kernel_id, hipEvent_t *start, hipEvent_t *stop);
+
+template <typename Args>
+hipError_t launch(void (*kernel)(Args), int kernel_id, uint32_t grid, int block,
+                  hipStream_t stream, const Args &args) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (timing_events(kernel_id, &e0, &e1))
+        hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(block), 0, stream, e0, e1, 0, args);
+    else
+        kernel<<<dim3(grid), dim3(block), 0, stream>>>(args);
+    return hipGetLastError();
+}
+
+}  // namespace adt

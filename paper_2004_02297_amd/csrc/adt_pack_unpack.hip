@@ -22,6 +22,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "adt_launch.h"
 #include "adt_tables.h"
 
 namespace adt {
@@ -337,20 +338,14 @@ __global__ __launch_bounds__(kBlock) void unpack_kernel(const PackArgs a) {
 
 hipError_t launch_pack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
                        hipStream_t stream) {
-    if (inline_table)
-        pack_kernel<true><<<dim3(n_tiles), dim3(kBlock), 0, stream>>>(a);
-    else
-        pack_kernel<false><<<dim3(n_tiles), dim3(kBlock), 0, stream>>>(a);
-    return hipGetLastError();
+    return inline_table ? launch(pack_kernel<true>, kKernelPack, n_tiles, kBlock, stream, a)
+                        : launch(pack_kernel<false>, kKernelPack, n_tiles, kBlock, stream, a);
 }
 
 hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
                          hipStream_t stream) {
-    if (inline_table)
-        unpack_kernel<true><<<dim3(n_tiles), dim3(kBlock), 0, stream>>>(a);
-    else
-        unpack_kernel<false><<<dim3(n_tiles), dim3(kBlock), 0, stream>>>(a);
-    return hipGetLastError();
+    return inline_table ? launch(unpack_kernel<true>, kKernelUnpack, n_tiles, kBlock, stream, a)
+                        : launch(unpack_kernel<false>, kKernelUnpack, n_tiles, kBlock, stream, a);
 }
 
 }  // namespace adt

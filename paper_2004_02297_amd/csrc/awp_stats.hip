@@ -8,13 +8,14 @@
 //      keeps four running sums; a wave combines its lanes with xor-shuffles,
 //      the block combines its four waves through LDS, and one partial
 //      {sum of squares, largest magnitude} per tile goes to scratch memory.
-//   2. final kernel: one block per layer adds that layer's partials in a fixed
-//      order and writes {sum, sqrt(sum), max |w|}.
+//   2. final kernel: one block of 1024 threads per layer adds that layer's
+//      partials in a fixed order and writes {sum, sqrt(sum), max |w|}.
 // No atomics: the order of every addition is fixed by the indices alone, so
 // the result is bit-identical from run to run.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "adt_launch.h"
 #include "adt_tables.h"
 
 namespace adt {
@@ -121,46 +122,71 @@ __global__ __launch_bounds__(kBlock) void stats_partial_kernel(const StatsArgs a
                   &a.partial_absmax[block]);
 }
 
+constexpr int kFinalBlock = 1024;
+constexpr int kFinalWaves = kFinalBlock / kWave;
+
 template <bool INLINE>
-__global__ __launch_bounds__(kBlock) void stats_final_kernel(const StatsFinalArgs a) {
+__global__ __launch_bounds__(kFinalBlock) void stats_final_kernel(const StatsFinalArgs a) {
     const uint32_t *tile_off = INLINE ? a.inl_tile_off : a.dev_tile_off;
     const int layer = (int)blockIdx.x;
     const uint32_t begin = tile_off[layer], end = tile_off[layer + 1];
+    // Thread t adds partials begin+t, begin+t+1024, ... in that order; four
+    // independent loads are in flight per round.
     double acc = 0.0;
     uint32_t mag = 0u;
-    for (uint32_t i = begin + threadIdx.x; i < end; i += kBlock) {
-        acc += a.partial_sumsq[i];
-        const uint32_t m = a.partial_absmax[i];
-        mag = m > mag ? m : mag;
+    for (uint32_t i = begin + threadIdx.x; i < end; i += 4 * kFinalBlock) {
+        double v[4];
+        uint32_t m[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t k = i + j * kFinalBlock;
+            const bool ok = k < end;
+            v[j] = ok ? a.partial_sumsq[k] : 0.0;
+            m[j] = ok ? a.partial_absmax[k] : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            acc += v[j];
+            mag = m[j] > mag ? m[j] : mag;
+        }
     }
-    __shared__ double tot_sum;
-    __shared__ uint32_t tot_mag;
-    block_combine(acc, mag, &tot_sum, &tot_mag);
+    __shared__ double wsum[kFinalWaves];
+    __shared__ uint32_t wmag[kFinalWaves];
+    acc = wave_sum(acc);
+    mag = wave_max(mag);
+    if ((threadIdx.x & 63) == 0) {
+        wsum[threadIdx.x >> 6] = acc;
+        wmag[threadIdx.x >> 6] = mag;
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
+        double tot = 0.0;
+        uint32_t tm = 0u;
+#pragma unroll
+        for (int i = 0; i < kFinalWaves; ++i) {
+            tot += wsum[i];
+            tm = wmag[i] > tm ? wmag[i] : tm;
+        }
         double *o = a.stats_out + (int64_t)layer * 3;
-        const double absmax = (double)__uint_as_float(tot_mag);
-        // a NaN weight poisons the sum as well; keep the three outputs consistent
-        o[0] = tot_sum;
-        o[1] = sqrt(tot_sum);
-        o[2] = absmax;
+        o[0] = tot;
+        o[1] = sqrt(tot);
+        o[2] = (double)__uint_as_float(tm);   // NaN bits stay NaN
     }
 }
 
 hipError_t launch_stats(const StatsArgs &a, const StatsFinalArgs &f, uint32_t n_tiles,
                         bool inline_table, hipStream_t stream) {
     if (n_tiles > 0) {
-        if (inline_table)
-            stats_partial_kernel<true><<<dim3(n_tiles), dim3(kBlock), 0, stream>>>(a);
-        else
-            stats_partial_kernel<false><<<dim3(n_tiles), dim3(kBlock), 0, stream>>>(a);
-        hipError_t e = hipGetLastError();
+        hipError_t e =
+            inline_table
+                ? launch(stats_partial_kernel<true>, kKernelStatsPartial, n_tiles, kBlock, stream, a)
+                : launch(stats_partial_kernel<false>, kKernelStatsPartial, n_tiles, kBlock, stream, a);
         if (e != hipSuccess) return e;
     }
-    if (inline_table)
-        stats_final_kernel<true><<<dim3(f.n_layers), dim3(kBlock), 0, stream>>>(f);
-    else
-        stats_final_kernel<false><<<dim3(f.n_layers), dim3(kBlock), 0, stream>>>(f);
-    return hipGetLastError();
+    return inline_table ? launch(stats_final_kernel<true>, kKernelStatsFinal, (uint32_t)f.n_layers,
+                                 kFinalBlock, stream, f)
+                        : launch(stats_final_kernel<false>, kKernelStatsFinal,
+                                 (uint32_t)f.n_layers, kFinalBlock, stream, f);
 }
 
 }  // namespace adt
