@@ -118,26 +118,40 @@ def main() -> int:
         adt.adt_unpack(packed, off, rb, out=w_out)
         return rb
 
-    for _ in range(args.warmup):
+    # The HIP runtime stalls once for tens of milliseconds somewhere in the first
+    # few hundred launches of a process (seen at launch ~250, never again in 3000
+    # steps).  PRIME_STEPS untimed passes before the warm-up keep that one-time
+    # event out of the timed region whatever --warmup is.
+    PRIME_STEPS = 150
+    rb = target_bytes
+    for _ in range(PRIME_STEPS + args.warmup):
         rb = step()
     torch.cuda.synchronize()
     assert np.array_equal(rb, target_bytes), "AWP state drifted from the workload's byte counts"
 
-    # Exact kernel durations over the timed region: every launch carries its
-    # dispatch's begin / end timestamps (HIP events bound to the launch, on the
-    # launch stream).
-    adt.adt_timing_enable(True)
+    # Exact kernel durations inside the timed region: on every TIMED_EVERY-th
+    # step each launch carries its dispatch's begin / end timestamps (HIP events
+    # bound to the launch, on the launch stream).  Sampling keeps the host cost
+    # of such launches (about 10 us each) out of most steps.
+    TIMED_EVERY = 4
+    n_sampled = (args.steps + TIMED_EVERY - 1) // TIMED_EVERY
+    adt.adt_timing_enable(True, 4 * n_sampled)
+    adt.adt_timing_enable(False)
     adt.adt_timing_read()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
+        sampled = k % TIMED_EVERY == 0
+        if sampled:
+            adt.adt_timing_enable(True)
         rb = step()
+        if sampled:
+            adt.adt_timing_enable(False)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     timing = adt.adt_timing_read()
-    adt.adt_timing_enable(False)
     assert np.array_equal(rb, target_bytes)
-    assert all(timing[k]["launches"] == args.steps for k in timing), timing
+    assert all(timing[k]["launches"] == n_sampled for k in timing), timing
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
@@ -146,7 +160,7 @@ def main() -> int:
     bytes_stats = 4.0 * N
 
     def kern(names, nbytes):
-        avg = sum(timing[n]["total_ms"] for n in names) / args.steps
+        avg = sum(timing[n]["total_ms"] for n in names) / n_sampled
         return {"avg_ms": round(avg, 5),
                 "min_ms": round(sum(timing[n]["min_ms"] for n in names), 5),
                 "max_ms": round(sum(timing[n]["max_ms"] for n in names), 5),
@@ -183,6 +197,9 @@ def main() -> int:
         "pack_unpack_hbm_frac": round(2 * bytes_adt / t_pu / 1e6 / HBM_PEAK_GBPS, 4),
         "stats_fp32_gbps": kernels["awp_layer_stats"]["gbps"],
         "kernels": kernels,
+        "priming_steps": PRIME_STEPS,
+        "kernel_timing": "dispatch begin/end timestamps on %d of the %d timed steps" % (
+            n_sampled, args.steps),
         "kernel_ms_per_step": round(t_kernels, 5),
         "host_and_sync_ms_per_step": round(ms_per_step - t_kernels, 5),
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved,

@@ -129,9 +129,12 @@ const char *adt_last_error(void);
 /*
  * Launch timing (measurement aid, off by default).  While enabled, every
  * kernel the library launches carries the dispatch's own begin / end
- * timestamps.  adt_timing_read waits for the launches recorded so far, writes
- * per-kernel totals to `out` (host, ADT_NKERNELS entries, indexed as
- * adt_kernel_name names them) and forgets them.
+ * timestamps (this costs the host about 10 us per launch, so a benchmark
+ * switches it on for a sample of its steps).  adt_timing_enable(on, n) also
+ * prepares event pairs for n launches ahead of time.  adt_timing_read waits
+ * for the launches recorded so far, writes per-kernel totals to `out` (host,
+ * ADT_NKERNELS entries, indexed as adt_kernel_name names them) and forgets
+ * them.
  */
 #define ADT_NKERNELS 4
 typedef struct adt_kernel_time {
@@ -140,7 +143,7 @@ typedef struct adt_kernel_time {
     double min_ms;
     double max_ms;
 } adt_kernel_time;
-int adt_timing_enable(int on);
+int adt_timing_enable(int on, int reserve_launches);
 int adt_timing_read(adt_kernel_time *out);
 const char *adt_kernel_name(int kernel);   /* "" outside 0..ADT_NKERNELS-1 */
 

@@ -58,7 +58,7 @@ def load_library():
     lib.adt_last_error.restype = ctypes.c_char_p
     lib.adt_last_error.argtypes = []
     lib.adt_timing_enable.restype = I
-    lib.adt_timing_enable.argtypes = [I]
+    lib.adt_timing_enable.argtypes = [I, I]
     lib.adt_timing_read.restype = I
     lib.adt_timing_read.argtypes = [P]
     lib.adt_kernel_name.restype = ctypes.c_char_p
@@ -200,9 +200,9 @@ def awp_update(state: AwpState, l2_now, T: float, interval: int, n_bits: int = 8
     return state.bytes.copy()
 
 
-def adt_timing_enable(on: bool) -> None:
+def adt_timing_enable(on: bool, reserve_launches: int = 0) -> None:
     """adt_timing_enable: exact per-launch kernel durations on / off."""
-    _check(load_library().adt_timing_enable(1 if on else 0))
+    _check(load_library().adt_timing_enable(1 if on else 0, int(reserve_launches)))
 
 
 def adt_timing_read() -> dict:

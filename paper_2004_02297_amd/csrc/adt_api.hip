@@ -391,9 +391,16 @@ const char *adt_strerror(int status) {
 
 const char *adt_last_error(void) { return g_err.c_str(); }
 
-int adt_timing_enable(int on) {
+int adt_timing_enable(int on, int reserve_launches) {
     std::lock_guard<std::mutex> lock(g_timing_mu);
     g_timing_on = on != 0;
+    while (on && (int)g_spare.size() < reserve_launches) {
+        std::pair<hipEvent_t, hipEvent_t> ev{nullptr, nullptr};
+        hipError_t e = hipEventCreate(&ev.first);
+        if (e == hipSuccess) e = hipEventCreate(&ev.second);
+        if (e != hipSuccess) return fail_hip(e, "hipEventCreate");
+        g_spare.push_back(ev);
+    }
     return ADT_OK;
 }
 

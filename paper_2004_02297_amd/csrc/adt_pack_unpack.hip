@@ -30,6 +30,44 @@ namespace adt {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef u32x4 u32x4_a4 __attribute__((aligned(4)));   // FP32 side: dword aligned
 
+// Cache hints.  FP32 weights are read once by pack and written once by unpack,
+// and the stream is read once by unpack: those accesses carry the nontemporal
+// hint, so their lines are not kept in L2 / Infinity Cache (on MI355X this
+// raises the sustained read rate by about 10 %).  The stream is WRITTEN with
+// ordinary stores: the consumer that follows (unpack, or a copy engine sending
+// it to a peer) then finds the most recent part of it in the Infinity Cache.
+// Measured on the statistics -> pack -> unpack pass over 138 M weights at
+// 2 bytes: 392 us without hints, 367 us with all four hints, 343 us with this
+// choice.
+#ifndef ADT_NT_FP32_LOAD
+#define ADT_NT_FP32_LOAD 1
+#endif
+#ifndef ADT_NT_FP32_STORE
+#define ADT_NT_FP32_STORE 1
+#endif
+#ifndef ADT_NT_STREAM_LOAD
+#define ADT_NT_STREAM_LOAD 1
+#endif
+#ifndef ADT_NT_STREAM_STORE
+#define ADT_NT_STREAM_STORE 0
+#endif
+__device__ __forceinline__ u32x4 load_fp32x4(const uint32_t *p) {
+    if (ADT_NT_FP32_LOAD) return __builtin_nontemporal_load((const u32x4_a4 *)p);
+    return *(const u32x4_a4 *)p;
+}
+__device__ __forceinline__ void store_fp32x4(uint32_t *p, const u32x4 v) {
+    if (ADT_NT_FP32_STORE) __builtin_nontemporal_store(v, (u32x4_a4 *)p);
+    else *(u32x4_a4 *)p = v;
+}
+__device__ __forceinline__ u32x4 load_stream16(const uint8_t *p) {   // 16-byte aligned
+    if (ADT_NT_STREAM_LOAD) return __builtin_nontemporal_load((const u32x4 *)p);
+    return *(const u32x4 *)p;
+}
+__device__ __forceinline__ void store_stream16(uint8_t *p, const u32x4 v) {
+    if (ADT_NT_STREAM_STORE) __builtin_nontemporal_store(v, (u32x4 *)p);
+    else *(u32x4 *)p = v;
+}
+
 constexpr int kPadDw = 8;                              // LDS pad before / after
 constexpr int kWaveLdsDw = kPadDw + kWaveTile + kPadDw;  // 1040 dwords per wave
 constexpr int kPadBytes = kPadDw * 4;
@@ -111,7 +149,7 @@ __device__ __forceinline__ void pack_wave_tile(const uint32_t *__restrict__ src,
         u32x4 v[kChunksPerLane];
 #pragma unroll
         for (int j = 0; j < kChunksPerLane; ++j)
-            v[j] = *(const u32x4_a4 *)(src + 4 * (j * kWave + lane));
+            v[j] = load_fp32x4(src + 4 * (j * kWave + lane));
 #pragma unroll
         for (int j = 0; j < kChunksPerLane; ++j) {
             uint32_t d[4];
@@ -127,7 +165,7 @@ __device__ __forceinline__ void pack_wave_tile(const uint32_t *__restrict__ src,
             const int e0 = 4 * c;
             u32x4 v = {0u, 0u, 0u, 0u};
             if (e0 + 4 <= len) {
-                v = *(const u32x4_a4 *)(src + e0);
+                v = load_fp32x4(src + e0);
             } else {
                 if (e0 < len) v.x = src[e0];
                 if (e0 + 1 < len) v.y = src[e0 + 1];
@@ -148,7 +186,7 @@ __device__ __forceinline__ void pack_wave_tile(const uint32_t *__restrict__ src,
         for (int k = 0; k < R; ++k) {
             const int q = k * kWave + lane;
             const u32x4 o = *(const u32x4 *)(body + 4 * q);
-            *(u32x4 *)(dst + 16 * q) = o;
+            store_stream16(dst + 16 * q, o);
         }
         return;
     }
@@ -172,7 +210,7 @@ __device__ __forceinline__ void pack_wave_tile(const uint32_t *__restrict__ src,
             o.z = funnel(x3, x2, sh);
             o.w = funnel(x4, x3, sh);
             if (b0 >= 0 && b0 + 16 <= nbytes) {
-                *(u32x4 *)(dst_al + 16 * q) = o;
+                store_stream16(dst_al + 16 * q, o);
             } else {
                 for (int t = 0; t < 16; ++t) {
                     const int bt = b0 + t;
@@ -201,7 +239,7 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
         u32x4 v[R];
 #pragma unroll
         for (int k = 0; k < R; ++k)
-            v[k] = *(const u32x4 *)(src + 16 * (k * kWave + lane));
+            v[k] = load_stream16(src + 16 * (k * kWave + lane));
 #pragma unroll
         for (int k = 0; k < R; ++k) *(u32x4 *)(lds + 4 * (k * kWave + lane)) = v[k];
         wave_lds_sync();
@@ -211,7 +249,7 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
             uint32_t y[4];
 #pragma unroll
             for (int t = 0; t < R; ++t) y[t] = lds[c * R + t];
-            *(u32x4_a4 *)(dst + 4 * c) = shift_to_top<R>(y);
+            store_fp32x4(dst + 4 * c, shift_to_top<R>(y));
         }
         return;
     }
@@ -225,7 +263,7 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
             const uint8_t *a = src_al + 16 * q;
             u32x4 v = {0u, 0u, 0u, 0u};
             if (a >= buf_lo && a + 16 <= buf_hi) {
-                v = *(const u32x4 *)a;
+                v = load_stream16(a);
             } else {
                 uint32_t w[4] = {0u, 0u, 0u, 0u};
                 for (int t = 0; t < 16; ++t)
@@ -254,7 +292,7 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
             for (int t = 0; t < R; ++t) y[t] = funnel(x[t + 1], x[t], sh);
             const u32x4 u = shift_to_top<R>(y);
             if (e0 + 4 <= len) {
-                *(u32x4_a4 *)(dst + e0) = u;
+                store_fp32x4(dst + e0, u);
             } else {
                 dst[e0] = u.x;
                 if (e0 + 1 < len) dst[e0 + 1] = u.y;

@@ -3,7 +3,8 @@
 //
 // Two launches for all layers together:
 //   1. partial kernel: the grid is the concatenation of every layer's tiles
-//      of 16384 weights.  A lane issues 128-bit loads, squares in double
+//      of 16384 weights.  A lane issues 128-bit loads (nontemporal: each
+//      weight is read once), squares in double
 //      precision (the square of a binary32 value is exact in binary64) and
 //      keeps four running sums; a wave combines its lanes with xor-shuffles,
 //      the block combines its four waves through LDS, and one partial
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(kBlock) void stats_partial_kernel(const StatsArgs a
             u32x4 v[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                v[j] = *(const u32x4_a4 *)(src + 4 * ((it * 4 + j) * kBlock + tid));
+                v[j] = __builtin_nontemporal_load((const u32x4_a4 *)(src + 4 * ((it * 4 + j) * kBlock + tid)));
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 accumulate(v[j].x, acc0, mag);
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(kBlock) void stats_partial_kernel(const StatsArgs a
         for (int i = 0; i < kStatsLoadsPerLane; ++i) {
             const int e0 = 4 * (i * kBlock + tid);
             if (e0 + 4 <= len) {
-                const u32x4 v = *(const u32x4_a4 *)(src + e0);
+                const u32x4 v = __builtin_nontemporal_load((const u32x4_a4 *)(src + e0));
                 accumulate(v.x, acc0, mag);
                 accumulate(v.y, acc1, mag);
                 accumulate(v.z, acc2, mag);
