@@ -71,6 +71,12 @@ def main() -> int:
     ap.add_argument("--workload", default="vgg16_all2", choices=sorted(WORKLOADS))
     ap.add_argument("--cpu-seconds", type=float, default=10.0,
                     help="lower bound on the CPU-oracle timing loop (0 = skip)")
+    ap.add_argument("--prime", type=int, default=150,
+                    help="untimed passes before the warm-up (see PRIME_STEPS below)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region, run one plain device copy of the weight "
+                         "buffer (4N bytes read, 4N written): the known-size kernel that "
+                         "rocprofv3 counter runs are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no multi-GPU "
@@ -122,7 +128,7 @@ def main() -> int:
     # few hundred launches of a process (seen at launch ~250, never again in 3000
     # steps).  PRIME_STEPS untimed passes before the warm-up keep that one-time
     # event out of the timed region whatever --warmup is.
-    PRIME_STEPS = 150
+    PRIME_STEPS = max(args.prime, 0)
     rb = target_bytes
     for _ in range(PRIME_STEPS + args.warmup):
         rb = step()
@@ -154,6 +160,9 @@ def main() -> int:
     assert all(timing[k]["launches"] == n_sampled for k in timing), timing
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    if args.calibrate_copy:
+        w_out.copy_(w)
+        torch.cuda.synchronize()
 
     sizes = np.diff(off)
     bytes_adt = float(np.sum(sizes * (4 + target_bytes.astype(np.int64))))   # per ADT launch
