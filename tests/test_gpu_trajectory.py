@@ -1,0 +1,95 @@
+"""AWP trajectory on the GPU against the oracle (needs a GPU).
+
+VGG-16-shaped weights take 200 steps of a multiplicative random walk
+(w += N(0, (1e-3 |w|)^2), generated on the device: input generation, not part
+of the method).  Every step runs awp_layer_stats, the AWP rule, adt_pack and
+adt_unpack.  The library's rule driven by GPU statistics must take the same
+decisions as the oracle's rule driven by oracle statistics of the same weights;
+the packed stream and the unpacked weights are compared bit for bit on every
+step where a byte count changed and on every 20th step.
+
+The paper's own thresholds were tuned on real training (T = -2e-3 and
+INTERVAL = 4000 for VGG) and cannot fire within 200 steps; that run is checked
+to stay at one byte everywhere.  A second, synthetic parameter set (T = 0,
+INTERVAL = 20, N = 8, 8 initial bits) lets small layers climb to wider formats
+while the large fully-connected layers stay narrow, so the byte assignment
+becomes mixed along the way.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+STEPS = 200
+
+
+def test_awp_trajectory_vgg16():
+    import paper_2004_02297_amd as adt
+    adt.load_library()
+
+    ws = workloads.make_weight_set("vgg16")
+    off, L, N = ws.layer_offsets, ws.n_layers, ws.n_weights
+    w = torch.from_numpy(ws.weights).cuda()
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    back = torch.empty_like(w)
+    packed = torch.empty(4 * N, dtype=torch.uint8, device="cuda")
+    stats_dev = torch.empty((L, 3), dtype=torch.float64, device="cuda")
+
+    syn = dict(T=0.0, interval=20, n_bits=8)
+    pap = dict(T=-2e-3, interval=4000, n_bits=8)
+    g_syn, o_syn = adt.AwpState(L, 8), oracle.AwpState(L, 8)
+    g_pap, o_pap = adt.AwpState(L, 8), oracle.AwpState(L, 8)
+
+    prev_rb = None
+    changes = 0
+    checked = 0
+    for step in range(STEPS):
+        if step:
+            noise = torch.randn(N, generator=gen, device="cuda", dtype=torch.float32)
+            w.addcmul_(noise, w.abs(), value=1e-3)
+            del noise
+        hw = w.cpu().numpy()
+
+        adt.awp_layer_stats(w, off, out=stats_dev)
+        g_stats = stats_dev.cpu().numpy()
+        o_stats = oracle.stats(hw, off)
+        np.testing.assert_allclose(g_stats, o_stats, rtol=1e-10, atol=0.0)
+        np.testing.assert_array_equal(g_stats[:, 2], o_stats[:, 2])
+
+        rb = adt.awp_update(g_syn, g_stats[:, 1], **syn)
+        orb = oracle.awp_update(o_syn, o_stats[:, 1], **syn)
+        if not np.array_equal(rb, orb):
+            # a decision may differ only where delta sits on the threshold to
+            # within the statistics' rounding error
+            prev = o_syn.l2_prev
+            pytest.fail(f"step {step}: byte decisions differ: {rb} vs {orb}; norms {prev}")
+        assert np.array_equal(g_syn.bits, o_syn.bits) and np.array_equal(g_syn.counter, o_syn.counter)
+        rb_p = adt.awp_update(g_pap, g_stats[:, 1], **pap)
+        assert np.array_equal(rb_p, oracle.awp_update(o_pap, o_stats[:, 1], **pap))
+
+        changed = prev_rb is not None and not np.array_equal(rb, prev_rb)
+        changes += int(changed)
+        size = adt.adt_packed_size(off, rb)
+        adt.adt_pack(w, off, rb, out=packed)
+        adt.adt_unpack(packed, off, rb, out=back)      # separate buffer: w stays full precision
+        if changed or step % 20 == 0 or step == STEPS - 1:
+            exp_stream = oracle.pack(hw, off, rb)
+            assert size == exp_stream.size
+            assert np.array_equal(packed[:size].cpu().numpy(), exp_stream), f"step {step}"
+            assert np.array_equal(back.view(torch.int32).cpu().numpy(),
+                                  oracle.unpack(exp_stream, off, rb).view(np.int32)), f"step {step}"
+            checked += 1
+        prev_rb = rb
+
+    # the paper's constants: nothing can fire in 200 steps
+    assert g_pap.bits.tolist() == [8] * L
+    # synthetic constants: a mixed assignment has emerged, big layers stay narrow
+    final = g_syn.bits // 8
+    assert changes >= 3 and checked >= 12
+    assert final.max() >= 2 and final.min() == 1, final
+    assert final[13] == 1, "the 102M-weight layer's norm grows steadily; it must stay at 1 byte"
