@@ -1,17 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the AWP/ADT hot path on one MI355X.
 
-One step = one pass of the whole path over a synthetic CNN-shaped weight set
-that is already resident in HBM:
-    awp_layer_stats -> copy of L x 3 doubles to the host -> awp_update (host,
-    scalar) -> adt_pack -> adt_unpack (into a separate FP32 buffer).
+One step = one pass of the whole path (per-layer statistics -> AWP rule ->
+Bitpack -> Bitunpack into a separate FP32 buffer) over a synthetic CNN-shaped
+weight set that is already resident in HBM.  Two implementations of the same
+pass are timed, each over its own K steps after W warm-up steps:
+
+  plan path   (the headline): awp_adt_step — device-resident AWP state, one
+              fused kernel that reads the weights once, no host round trip.
+  three calls (reported under "three_call_path"): awp_layer_stats -> copy of
+              L x 3 doubles to the host -> awp_update on the host -> adt_pack
+              -> adt_unpack.
+
 Prints ONE JSON line.  `value` is FP32 weight bytes through the whole pass per
-second (4 N / step time).  Per-kernel durations are the dispatches' own begin /
-end timestamps (HIP events bound to each launch on its stream, read through
-the library's launch-timing calls) over the timed region; the roofline entry prices the
-slower of the two ADT kernels against the 8 TB/s HBM peak with algorithmic
-bytes (4 + r per weight).  The CPU oracle is timed beside it on a bounded
-number of passes over the same weight set.
+second (4 N / step time).  Kernel durations are the dispatches' own begin / end
+timestamps (HIP events bound to each launch on its stream, read through the
+library's launch-timing calls) on a sample of the timed steps.  The roofline
+entry prices the dominant kernel against the 8 TB/s HBM peak with algorithmic
+bytes.  The CPU oracle is timed beside it on full passes over the same weights.
 """
 from __future__ import annotations
 
@@ -29,9 +35,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+TIMED_EVERY = 4          # launch timing is switched on for every 4th timed step
 
 WORKLOADS = {
-    # name: (weight set, byte-count variant, start bits for the AWP state)
+    # name: (weight set, byte-count variant)
     "vgg16_all2": ("vgg16", "all2"),
     "vgg16_all3": ("vgg16", "all3"),
     "vgg16_all1": ("vgg16", "all1"),
@@ -63,6 +70,11 @@ def recorded_traffic(kernel: str, workload: str):
     return rec.get("traffic_bytes", {}).get(workload, {}).get(kernel)
 
 
+def plan_tiles(sizes) -> int:
+    """Block tiles (4096 weights) of the plan's fused kernel = partials per step."""
+    return int(np.sum((np.asarray(sizes) + 4095) // 4096))
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -72,15 +84,21 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=10.0,
                     help="lower bound on the CPU-oracle timing loop (0 = skip)")
     ap.add_argument("--prime", type=int, default=150,
-                    help="untimed passes before the warm-up (see PRIME_STEPS below)")
+                    help="untimed passes before the first warm-up (see PRIME_STEPS below)")
+    ap.add_argument("--paths", default="plan,calls",
+                    help="which implementations to time: plan, calls or plan,calls")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="after the timed region, run one plain device copy of the weight "
+                    help="after the timed regions, run one plain device copy of the weight "
                          "buffer (4N bytes read, 4N written): the known-size kernel that "
                          "rocprofv3 counter runs are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no multi-GPU "
               "path); run with --gpus 1", file=sys.stderr)
+        return 2
+    paths = [p for p in args.paths.split(",") if p]
+    if not paths or any(p not in ("plan", "calls") for p in paths):
+        print("bench.py: --paths takes plan, calls or plan,calls", file=sys.stderr)
         return 2
 
     import torch
@@ -99,100 +117,146 @@ def main() -> int:
     off = ws.layer_offsets
     L, N = ws.n_layers, ws.n_weights
     target_bytes = workloads.config_bytes(set_name, variant)
+    start_bits = target_bytes.astype(np.int32) * 8
 
-    # AWP state: the paper's VGG threshold and interval (Section V-A).  The
+    # AWP parameters: the paper's VGG threshold and interval (Section V-A).  The
     # weight set does not change between steps, so delta = 0 >= T on every step
     # and each layer stays at its starting precision: the byte counts the
     # workload names are exactly what the rule hands to pack/unpack.
     T, INTERVAL, N_BITS = -2e-3, 4000, 8
-    state = adt.AwpState(L)
-    state.bits[:] = target_bytes.astype(np.int32) * 8
 
     w = torch.from_numpy(ws.weights).cuda()
-    packed = torch.empty(adt.adt_packed_size(off, target_bytes), dtype=torch.uint8, device="cuda")
+    packed = torch.empty(4 * N, dtype=torch.uint8, device="cuda")
     w_out = torch.empty_like(w)
     stats_dev = torch.empty((L, adt.AWP_NSTATS), dtype=torch.float64, device="cuda")
     stats_host = torch.empty((L, adt.AWP_NSTATS), dtype=torch.float64, pin_memory=True)
     stream = torch.cuda.current_stream()
+    sizes = np.diff(off)
+    rsum = target_bytes.astype(np.int64)
 
-    def step():
+    state = adt.AwpState(L)
+    state.bits[:] = start_bits
+
+    def step_calls():
         adt.awp_layer_stats(w, off, out=stats_dev)
         stats_host.copy_(stats_dev, non_blocking=True)
         stream.synchronize()
         rb = adt.awp_update(state, stats_host[:, 1].numpy(), T, INTERVAL, N_BITS)
         adt.adt_pack(w, off, rb, out=packed)
         adt.adt_unpack(packed, off, rb, out=w_out)
-        return rb
+
+    plan = adt.AwpPlan(off, T, INTERVAL, N_BITS, init_bits=start_bits)
+
+    def step_plan():
+        plan.step(w, packed, w_out)
 
     # The HIP runtime stalls once for tens of milliseconds somewhere in the first
-    # few hundred launches of a process (seen at launch ~250, never again in 3000
-    # steps).  PRIME_STEPS untimed passes before the warm-up keep that one-time
-    # event out of the timed region whatever --warmup is.
+    # few hundred operations of a kind in a process (seen around the 85th pass of
+    # the three-call path, never again in 3000 passes).  PRIME_STEPS untimed
+    # passes of a path before its warm-up keep that one-time event out of its
+    # timed region whatever --warmup is.
     PRIME_STEPS = max(args.prime, 0)
-    rb = target_bytes
-    for _ in range(PRIME_STEPS + args.warmup):
-        rb = step()
-    torch.cuda.synchronize()
-    assert np.array_equal(rb, target_bytes), "AWP state drifted from the workload's byte counts"
-
-    # Exact kernel durations inside the timed region: on every TIMED_EVERY-th
-    # step each launch carries its dispatch's begin / end timestamps (HIP events
-    # bound to the launch, on the launch stream).  Sampling keeps the host cost
-    # of such launches (about 10 us each) out of most steps.
-    TIMED_EVERY = 4
     n_sampled = (args.steps + TIMED_EVERY - 1) // TIMED_EVERY
-    adt.adt_timing_enable(True, 4 * n_sampled)
-    adt.adt_timing_enable(False)
-    adt.adt_timing_read()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        sampled = k % TIMED_EVERY == 0
-        if sampled:
-            adt.adt_timing_enable(True)
-        rb = step()
-        if sampled:
-            adt.adt_timing_enable(False)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    timing = adt.adt_timing_read()
-    assert np.array_equal(rb, target_bytes)
-    assert all(timing[k]["launches"] == n_sampled for k in timing), timing
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    def timed_region(step, prime):
+        for i in range(prime + args.warmup):
+            step()
+            if i % 32 == 31:
+                torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        adt.adt_timing_enable(True, 8 * n_sampled)    # prepare event pairs up front
+        adt.adt_timing_enable(False)
+        adt.adt_timing_read()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            sampled = k % TIMED_EVERY == 0
+            if sampled:
+                adt.adt_timing_enable(True)
+            step()
+            if sampled:
+                adt.adt_timing_enable(False)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return (t1 - t0) * 1e3 / args.steps, adt.adt_timing_read()
+
+    def kern(timing, names, nbytes):
+        avg = sum(timing[n]["total_ms"] / max(timing[n]["launches"], 1) for n in names)
+        return {"avg_ms": round(avg, 5),
+                "min_ms": round(sum(timing[n]["min_ms"] for n in names), 5),
+                "max_ms": round(sum(timing[n]["max_ms"] for n in names), 5),
+                "launches_timed": int(timing[names[0]]["launches"]),
+                "gbps": round(nbytes / avg / 1e6, 1),
+                "hbm_frac": round(nbytes / avg / 1e6 / HBM_PEAK_GBPS, 4)}
+
+    bytes_pack = float(np.sum(sizes * (4 + rsum)))            # per pack or unpack launch
+    bytes_stats = 4.0 * N
+    bytes_fused = float(np.sum(sizes * (8 + rsum)))           # read W, write stream + W'
+    unit = "GB/s of FP32 weights through one full pass (stats + AWP rule + pack + unpack)"
+    report = {}
+
+    if "plan" in paths:
+        ms, timing = timed_region(step_plan, PRIME_STEPS)
+        got = plan.read()
+        assert np.array_equal(got["bytes"], target_bytes), "AWP state drifted"
+        assert got["packed_size"] == int(np.sum(sizes * rsum))
+        kernels = {"fused_kernel": kern(timing, ["fused_kernel"], bytes_fused),
+                   "stats_final_kernel": kern(timing, ["stats_final_kernel"],
+                                              12.0 * plan_tiles(sizes)),
+                   "rule_kernel": kern(timing, ["rule_kernel"], 64.0 * L),
+                   "redo_kernel": kern(timing, ["redo_kernel"], 4.0)}
+        for k in ("stats_final_kernel", "rule_kernel", "redo_kernel"):   # latency bound
+            del kernels[k]["gbps"], kernels[k]["hbm_frac"]
+        t_k = sum(k["avg_ms"] for k in kernels.values())
+        report["plan"] = {
+            "value": round(4.0 * N / ms / 1e6, 2), "ms_per_step": round(ms, 5),
+            "kernels": kernels, "kernel_ms_per_step": round(t_k, 5),
+            "host_and_gaps_ms_per_step": round(ms - t_k, 5),
+            "moved_gbps_whole_step": round(bytes_fused / ms / 1e6, 1),
+            "hbm_frac_whole_step": round(bytes_fused / ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "roofline": {"bound": "hbm", "kernel": "fused_kernel",
+                         "achieved": kernels["fused_kernel"]["gbps"], "peak": HBM_PEAK_GBPS,
+                         "unit": "GB/s", "frac": kernels["fused_kernel"]["hbm_frac"],
+                         "algorithmic_bytes_per_launch": bytes_fused,
+                         "traffic": recorded_traffic("fused_kernel", args.workload)}}
+
+    if "calls" in paths:
+        ms, timing = timed_region(step_calls, PRIME_STEPS)
+        assert np.array_equal(state.bytes, target_bytes), "AWP state drifted"
+        kernels = {"adt_pack": kern(timing, ["pack_kernel"], bytes_pack),
+                   "adt_unpack": kern(timing, ["unpack_kernel"], bytes_pack),
+                   "awp_layer_stats": kern(timing, ["stats_partial_kernel", "stats_final_kernel"],
+                                           bytes_stats)}
+        dom = "adt_pack" if kernels["adt_pack"]["avg_ms"] >= kernels["adt_unpack"]["avg_ms"] \
+            else "adt_unpack"
+        t_pu = kernels["adt_pack"]["avg_ms"] + kernels["adt_unpack"]["avg_ms"]
+        t_k = t_pu + kernels["awp_layer_stats"]["avg_ms"]
+        report["calls"] = {
+            "value": round(4.0 * N / ms / 1e6, 2), "ms_per_step": round(ms, 5),
+            "kernels": kernels, "kernel_ms_per_step": round(t_k, 5),
+            "host_and_sync_ms_per_step": round(ms - t_k, 5),
+            "pack_unpack_fp32_gbps": round(4.0 * N / t_pu / 1e6, 1),
+            "pack_unpack_moved_gbps": round(2 * bytes_pack / t_pu / 1e6, 1),
+            "pack_unpack_hbm_frac": round(2 * bytes_pack / t_pu / 1e6 / HBM_PEAK_GBPS, 4),
+            "stats_fp32_gbps": kernels["awp_layer_stats"]["gbps"],
+            "roofline": {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["gbps"],
+                         "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": kernels[dom]["hbm_frac"],
+                         "algorithmic_bytes_per_launch": bytes_pack,
+                         "traffic": recorded_traffic(dom, args.workload)}}
+
     if args.calibrate_copy:
         w_out.copy_(w)
         torch.cuda.synchronize()
 
-    sizes = np.diff(off)
-    bytes_adt = float(np.sum(sizes * (4 + target_bytes.astype(np.int64))))   # per ADT launch
-    bytes_stats = 4.0 * N
-
-    def kern(names, nbytes):
-        avg = sum(timing[n]["total_ms"] for n in names) / n_sampled
-        return {"avg_ms": round(avg, 5),
-                "min_ms": round(sum(timing[n]["min_ms"] for n in names), 5),
-                "max_ms": round(sum(timing[n]["max_ms"] for n in names), 5),
-                "gbps": round(nbytes / avg / 1e6, 1),
-                "hbm_frac": round(nbytes / avg / 1e6 / HBM_PEAK_GBPS, 4)}
-
-    kernels = {"adt_pack": kern(["pack_kernel"], bytes_adt),
-               "adt_unpack": kern(["unpack_kernel"], bytes_adt),
-               "awp_layer_stats": kern(["stats_partial_kernel", "stats_final_kernel"], bytes_stats)}
-    dom = "adt_pack" if kernels["adt_pack"]["avg_ms"] >= kernels["adt_unpack"]["avg_ms"] \
-        else "adt_unpack"
-    achieved = kernels[dom]["gbps"]
-    t_pu = kernels["adt_pack"]["avg_ms"] + kernels["adt_unpack"]["avg_ms"]
-    t_kernels = t_pu + kernels["awp_layer_stats"]["avg_ms"]
-
+    head = report[paths[0]]
     result = {
         "metric": "ADT pack+unpack GB/s of FP32 weights (and % of HBM peak); AWP stats GB/s",
-        "value": round(4.0 * N / ms_per_step / 1e6, 2),
-        "unit": "GB/s of FP32 weights through one full pass (stats + AWP rule + pack + unpack)",
+        "value": head["value"],
+        "unit": unit,
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5),
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -200,28 +264,23 @@ def main() -> int:
         "data": "synthetic He-normal CNN-shaped FP32 weights, resident in HBM",
         "config": {"workload": args.workload, "n_weights": N, "n_layers": L,
                    "bytes_per_layer": target_bytes.tolist(),
-                   "packed_bytes": int(packed.numel())},
-        "pack_unpack_fp32_gbps": round(4.0 * N / t_pu / 1e6, 1),
-        "pack_unpack_moved_gbps": round(2 * bytes_adt / t_pu / 1e6, 1),
-        "pack_unpack_hbm_frac": round(2 * bytes_adt / t_pu / 1e6 / HBM_PEAK_GBPS, 4),
-        "stats_fp32_gbps": kernels["awp_layer_stats"]["gbps"],
-        "kernels": kernels,
+                   "packed_bytes": int(np.sum(sizes * rsum)),
+                   "path": "awp_adt_step (plan)" if paths[0] == "plan" else "three calls"},
         "priming_steps": PRIME_STEPS,
         "kernel_timing": "dispatch begin/end timestamps on %d of the %d timed steps" % (
             n_sampled, args.steps),
-        "kernel_ms_per_step": round(t_kernels, 5),
-        "host_and_sync_ms_per_step": round(ms_per_step - t_kernels, 5),
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved,
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "algorithmic_bytes_per_launch": bytes_adt,
-                     "traffic": recorded_traffic(dom, args.workload)},
+        "roofline": head["roofline"],
     }
+    for k, v in head.items():
+        if k not in ("value", "ms_per_step", "roofline"):
+            result[k] = v
+    if len(paths) > 1:
+        result["three_call_path" if paths[1] == "calls" else "plan_path"] = report[paths[1]]
 
     if args.cpu_seconds > 0:
         import oracle
         ostate = oracle.AwpState(L)
-        ostate.bits[:] = state.bits
+        ostate.bits[:] = start_bits
         passes, c0 = 0, time.perf_counter()
         while passes < 2 or time.perf_counter() - c0 < args.cpu_seconds:
             st = oracle.stats(ws.weights, off)
@@ -232,7 +291,7 @@ def main() -> int:
         c1 = time.perf_counter()
         result["cpu_baseline"] = {
             "value": round(4.0 * N * passes / (c1 - c0) / 1e9, 3),
-            "unit": result["unit"], "cores": 1, "kind": "oracle",
+            "unit": unit, "cores": 1, "kind": "oracle",
             "sample": "%d full passes (stats + rule + pack + unpack) of the scalar C oracle "
                       "over the same %s weight set, %.1f s" % (passes, args.workload, c1 - c0),
             "host_cpus_visible": os.cpu_count(),

@@ -120,6 +120,44 @@ int awp_update(const double *l2_now, double *l2_prev, int32_t *counter,
                int32_t *bits, uint8_t *bytes_out, int n_layers, double T,
                int interval, int n_bits, int is_first_batch);
 
+/*
+ * Plan: the whole pass with device-resident AWP state, asynchronous.
+ *
+ * A plan owns, on the current device, the per-layer tables, the AWP state
+ * (bits, interval counters, previous norms) and scratch for the statistics.
+ * awp_adt_step enqueues on `stream`, without waiting for the GPU, exactly what
+ *     awp_layer_stats(weights) -> awp_update(state) -> adt_pack(weights,
+ *     bytes) -> adt_unpack(packed, bytes) into weights_out
+ * computes in that order (Algorithm 1's order: the byte counts chosen from this
+ * batch's norms are the ones this batch is packed with), but reads the weights
+ * from HBM once: statistics, stream and truncated weights are produced by one
+ * kernel under the assumption that the byte counts of the previous batch still
+ * hold, the rule then runs on the device, and only if it changed a byte count
+ * (a few times per training run) are stream and truncated weights redone.
+ *   layer_offsets  host, as for adt_pack
+ *   init_bits      host, n_layers entries, or NULL for 8 bits everywhere
+ *                  (Section V-A: AWP starts at 8 bits)
+ *   T, interval, n_bits  parameters of Algorithm 1
+ *   weights        device, N floats, 4-byte aligned
+ *   packed         device, packed_capacity bytes; capacity must be at least
+ *                  4*N so that any byte assignment fits
+ *   weights_out    device, N floats, or NULL to skip the truncated copy; must
+ *                  not overlap weights or packed
+ * Calls on one plan must be issued from one thread at a time and on one stream
+ * (or on streams ordered by the caller).  The step allocates nothing.
+ * awp_plan_read waits for the steps enqueued so far and copies the state to
+ * host arrays (any pointer may be NULL): stats n_layers*AWP_NSTATS doubles,
+ * bits / counter / bytes n_layers entries, packed_size one value.
+ */
+typedef struct awp_plan awp_plan;
+int awp_plan_create(const int64_t *layer_offsets, int n_layers, const int32_t *init_bits,
+                    double T, int interval, int n_bits, awp_plan **plan_out);
+int awp_adt_step(awp_plan *plan, const float *weights, uint8_t *packed,
+                 int64_t packed_capacity, float *weights_out, adt_stream_t stream);
+int awp_plan_read(awp_plan *plan, double *stats, int32_t *bits, int32_t *counter,
+                  uint8_t *bytes, int64_t *packed_size);
+int awp_plan_destroy(awp_plan *plan);
+
 /* Text for a status code (static string). */
 const char *adt_strerror(int status);
 
@@ -136,7 +174,7 @@ const char *adt_last_error(void);
  * ADT_NKERNELS entries, indexed as adt_kernel_name names them) and forgets
  * them.
  */
-#define ADT_NKERNELS 4
+#define ADT_NKERNELS 7
 typedef struct adt_kernel_time {
     int64_t launches;
     double total_ms;

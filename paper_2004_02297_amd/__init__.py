@@ -6,7 +6,7 @@ on the weights runs in the library's gfx950 kernels.  There is no CPU fallback:
 if the library is missing, loading fails.
 """
 from .binding import (  # noqa: F401
-    AWP_NSTATS, AdtError, AwpState, adt_pack, adt_packed_size, adt_unpack,
+    AWP_NSTATS, AdtError, AwpPlan, AwpState, adt_pack, adt_packed_size, adt_unpack,
     awp_layer_stats, awp_update, lib_path, load_library, adt_timing_enable,
     adt_timing_read,
 )

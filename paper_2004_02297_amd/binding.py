@@ -14,7 +14,7 @@ import numpy as np
 from . import _build
 
 AWP_NSTATS = 3
-ADT_NKERNELS = 4
+ADT_NKERNELS = 7
 _lib = None
 
 
@@ -63,6 +63,14 @@ def load_library():
     lib.adt_timing_read.argtypes = [P]
     lib.adt_kernel_name.restype = ctypes.c_char_p
     lib.adt_kernel_name.argtypes = [I]
+    lib.awp_plan_create.restype = I
+    lib.awp_plan_create.argtypes = [P, I, P, ctypes.c_double, I, I, ctypes.POINTER(P)]
+    lib.awp_adt_step.restype = I
+    lib.awp_adt_step.argtypes = [P, P, P, I64, P, P]
+    lib.awp_plan_read.restype = I
+    lib.awp_plan_read.argtypes = [P, P, P, P, P, P]
+    lib.awp_plan_destroy.restype = I
+    lib.awp_plan_destroy.argtypes = [P]
     lib.adt_shutdown.restype = I
     lib.adt_shutdown.argtypes = []
     _lib = lib
@@ -213,3 +221,60 @@ def adt_timing_read() -> dict:
     return {lib.adt_kernel_name(k).decode(): {
         "launches": int(arr[k].launches), "total_ms": arr[k].total_ms,
         "min_ms": arr[k].min_ms, "max_ms": arr[k].max_ms} for k in range(ADT_NKERNELS)}
+
+
+class AwpPlan:
+    """awp_plan_*: device-resident AWP state; step() is one asynchronous pass
+    statistics -> rule -> pack -> unpack (see include/adt.h)."""
+
+    def __init__(self, layer_offsets, T: float, interval: int, n_bits: int = 8,
+                 init_bits=None):
+        self._lib = load_library()
+        off = _host(layer_offsets, np.int64)
+        self.n_layers = off.size - 1
+        self.n_weights = int(off[-1])
+        ib = None if init_bits is None else _host(init_bits, np.int32)
+        if ib is not None and ib.shape != (self.n_layers,):
+            raise ValueError("init_bits must have n_layers entries")
+        h = ctypes.c_void_p()
+        _check(self._lib.awp_plan_create(_hptr(off), self.n_layers, _hptr(ib), float(T),
+                                         int(interval), int(n_bits), ctypes.byref(h)))
+        self._h = h
+
+    def step(self, weights, packed, weights_out=None, stream=None) -> None:
+        """awp_adt_step; `packed` must hold at least 4 bytes per weight."""
+        import torch
+        w = _dev_tensor(weights, torch.float32, "weights")
+        p = _dev_tensor(packed, torch.uint8, "packed")
+        if w.numel() != self.n_weights:
+            raise ValueError("weights size does not match the plan")
+        o = None
+        if weights_out is not None:
+            o = _dev_tensor(weights_out, torch.float32, "weights_out")
+            if o.numel() != self.n_weights:
+                raise ValueError("weights_out size does not match the plan")
+        _check(self._lib.awp_adt_step(self._h, w.data_ptr() or None, p.data_ptr() or None,
+                                      p.numel(), None if o is None else (o.data_ptr() or None),
+                                      _stream(stream)))
+
+    def read(self) -> dict:
+        """awp_plan_read: waits for the enqueued steps, returns the state."""
+        L = self.n_layers
+        st = np.empty((L, AWP_NSTATS), np.float64)
+        bits, cnt = np.empty(L, np.int32), np.empty(L, np.int32)
+        rb, size = np.empty(L, np.uint8), np.zeros(1, np.int64)
+        _check(self._lib.awp_plan_read(self._h, _hptr(st), _hptr(bits), _hptr(cnt), _hptr(rb),
+                                       _hptr(size)))
+        return {"stats": st, "bits": bits, "counter": cnt, "bytes": rb,
+                "packed_size": int(size[0])}
+
+    def close(self) -> None:
+        if self._h is not None:
+            self._lib.awp_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

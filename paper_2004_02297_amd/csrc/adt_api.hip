@@ -9,6 +9,7 @@
 
 #include <map>
 #include <mutex>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -23,7 +24,29 @@ hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
                          hipStream_t stream);
 hipError_t launch_stats(const StatsArgs &a, const StatsFinalArgs &f, uint32_t n_tiles,
                         bool inline_table, hipStream_t stream);
+hipError_t launch_stats_final(const StatsFinalArgs &f, bool inline_table, hipStream_t stream);
+hipError_t launch_fused(const FusedArgs &a, bool write_w, hipStream_t stream);
+hipError_t launch_redo(const FusedArgs &a, bool write_w, hipStream_t stream);
+hipError_t launch_rule(const RuleArgs &a, hipStream_t stream);
 }  // namespace adt
+
+// A plan: device-resident tables + AWP state (see include/adt.h).
+struct awp_plan {
+    int device = 0;
+    int n_layers = 0;
+    int64_t n = 0;
+    uint32_t n_tiles = 0;
+    double T = 0.0;
+    int interval = 0, n_bits = 0;
+    int64_t steps = 0;
+    hipStream_t last_stream = nullptr;
+    char *block = nullptr;          // one device allocation holding all of the below
+    int64_t *elem_off = nullptr, *pack_off = nullptr, *packed_size = nullptr;
+    uint32_t *tile_off = nullptr, *partial_absmax = nullptr;
+    uint8_t *rbytes = nullptr;
+    int32_t *bits = nullptr, *counter = nullptr, *changed = nullptr;
+    double *l2_prev = nullptr, *stats = nullptr, *partial_sumsq = nullptr;
+};
 
 static_assert(ADT_NKERNELS == adt::kNumKernels, "adt.h and adt_launch.h disagree");
 
@@ -377,6 +400,186 @@ int awp_update(const double *l2_now, double *l2_prev, int32_t *counter, int32_t 
     return ADT_OK;
 }
 
+int awp_plan_create(const int64_t *layer_offsets, int n_layers, const int32_t *init_bits,
+                    double T, int interval, int n_bits, awp_plan **plan_out) {
+    if (!plan_out) return fail(ADT_EINVAL, "plan_out is null");
+    *plan_out = nullptr;
+    int rc = check_tables(layer_offsets, nullptr, false, n_layers);
+    if (rc) return rc;
+    if (interval < 1 || n_bits < 0) return fail(ADT_EINVAL, "interval < 1 or n_bits < 0");
+    const size_t L = (size_t)n_layers, L1 = L + 1;
+    std::vector<uint32_t> tile_off(L1);
+    rc = build_tile_off(layer_offsets, n_layers, adt::kBlockTile, tile_off.data());
+    if (rc) return rc;
+    std::vector<int32_t> bits(L);
+    std::vector<uint8_t> rb(L);
+    std::vector<int64_t> pack_off(L1);
+    int64_t p = 0;
+    for (size_t l = 0; l < L; ++l) {
+        const int32_t b = init_bits ? init_bits[l] : 8;
+        if (b < 1 || b > 32) return fail(ADT_EINVAL, "init_bits not in 1..32");
+        bits[l] = b;
+        rb[l] = (uint8_t)((b + 7) >> 3);
+        pack_off[l] = p;
+        p += (layer_offsets[l + 1] - layer_offsets[l]) * (int64_t)rb[l];
+    }
+    pack_off[L] = p;
+
+    awp_plan *pl = new (std::nothrow) awp_plan();
+    if (!pl) return fail(ADT_ENOMEM, "plan");
+    hipError_t e = hipGetDevice(&pl->device);
+    if (e != hipSuccess) { delete pl; return fail_hip(e, "hipGetDevice"); }
+    pl->n_layers = n_layers;
+    pl->n = layer_offsets[n_layers];
+    pl->n_tiles = tile_off[L];
+    pl->T = T;
+    pl->interval = interval;
+    pl->n_bits = n_bits;
+
+    // carve one allocation; 8-byte items first
+    size_t o = 0;
+    auto take = [&o](size_t bytes) { size_t at = o; o += align8(bytes); return at; };
+    const size_t o_elem = take(8 * L1), o_pack = take(8 * L1), o_psize = take(8);
+    const size_t o_prev = take(8 * L), o_stats = take(24 * L), o_psum = take(8 * (size_t)pl->n_tiles);
+    const size_t o_tile = take(4 * L1), o_pmax = take(4 * (size_t)pl->n_tiles);
+    const size_t o_bits = take(4 * L), o_cnt = take(4 * L), o_chg = take(4), o_rb = take(L);
+    const size_t total = o + 8;
+    e = hipMalloc((void **)&pl->block, total);
+    if (e != hipSuccess) { (void)hipGetLastError(); delete pl; return fail(ADT_ENOMEM, "plan tables"); }
+    char *b = pl->block;
+    pl->elem_off = (int64_t *)(b + o_elem);
+    pl->pack_off = (int64_t *)(b + o_pack);
+    pl->packed_size = (int64_t *)(b + o_psize);
+    pl->l2_prev = (double *)(b + o_prev);
+    pl->stats = (double *)(b + o_stats);
+    pl->partial_sumsq = (double *)(b + o_psum);
+    pl->tile_off = (uint32_t *)(b + o_tile);
+    pl->partial_absmax = (uint32_t *)(b + o_pmax);
+    pl->bits = (int32_t *)(b + o_bits);
+    pl->counter = (int32_t *)(b + o_cnt);
+    pl->changed = (int32_t *)(b + o_chg);
+    pl->rbytes = (uint8_t *)(b + o_rb);
+
+    e = hipMemset(b, 0, total);
+    if (e == hipSuccess) e = hipMemcpy(pl->elem_off, layer_offsets, 8 * L1, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(pl->pack_off, pack_off.data(), 8 * L1, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(pl->packed_size, &p, 8, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(pl->tile_off, tile_off.data(), 4 * L1, hipMemcpyHostToDevice);
+    if (e == hipSuccess && L) e = hipMemcpy(pl->bits, bits.data(), 4 * L, hipMemcpyHostToDevice);
+    if (e == hipSuccess && L) e = hipMemcpy(pl->rbytes, rb.data(), L, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        (void)hipFree(pl->block);
+        delete pl;
+        return fail_hip(e, "plan upload");
+    }
+    *plan_out = pl;
+    return ADT_OK;
+}
+
+int awp_adt_step(awp_plan *plan, const float *weights, uint8_t *packed,
+                 int64_t packed_capacity, float *weights_out, adt_stream_t stream) {
+    if (!plan) return fail(ADT_EINVAL, "plan is null");
+    hipStream_t hs = (hipStream_t)stream;
+    plan->last_stream = hs;
+    if (plan->n_layers == 0) return ADT_OK;
+    if (plan->n > 0) {
+        if (!weights || !packed) return fail(ADT_EINVAL, "null device pointer");
+        if (((uintptr_t)weights | (uintptr_t)weights_out) & 3u)
+            return fail(ADT_EALIGN, "FP32 buffer is not 4-byte aligned");
+        if (packed_capacity < 4 * plan->n)
+            return fail(ADT_EINVAL, "packed_capacity must be at least 4 bytes per weight");
+    }
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (dev != plan->device) return fail(ADT_EINVAL, "plan belongs to another device");
+
+    adt::FusedArgs a;
+    a.weights = (const uint32_t *)weights;
+    a.packed = packed;
+    a.weights_out = (uint32_t *)weights_out;
+    a.elem_off = plan->elem_off;
+    a.pack_off = plan->pack_off;
+    a.tile_off = plan->tile_off;
+    a.rbytes = plan->rbytes;
+    a.partial_sumsq = plan->partial_sumsq;
+    a.partial_absmax = plan->partial_absmax;
+    a.changed = plan->changed;
+    a.n_layers = plan->n_layers;
+    a.n_tiles = plan->n_tiles;
+    const bool write_w = weights_out != nullptr;
+
+    if (plan->n_tiles > 0) {
+        e = adt::launch_fused(a, write_w, hs);
+        if (e != hipSuccess) return fail_hip(e, "fused launch");
+    }
+    adt::StatsFinalArgs f;
+    f.partial_sumsq = plan->partial_sumsq;
+    f.partial_absmax = plan->partial_absmax;
+    f.stats_out = plan->stats;
+    f.n_layers = plan->n_layers;
+    f.dev_tile_off = plan->tile_off;
+    e = adt::launch_stats_final(f, false, hs);
+    if (e != hipSuccess) return fail_hip(e, "statistics final launch");
+
+    adt::RuleArgs r;
+    r.stats = plan->stats;
+    r.l2_prev = plan->l2_prev;
+    r.bits = plan->bits;
+    r.counter = plan->counter;
+    r.rbytes = plan->rbytes;
+    r.elem_off = plan->elem_off;
+    r.pack_off = plan->pack_off;
+    r.changed = plan->changed;
+    r.packed_size = plan->packed_size;
+    r.n_layers = plan->n_layers;
+    r.T = plan->T;
+    r.interval = plan->interval;
+    r.n_bits = plan->n_bits;
+    r.is_first = plan->steps == 0;
+    e = adt::launch_rule(r, hs);
+    if (e != hipSuccess) return fail_hip(e, "rule launch");
+    ++plan->steps;
+    if (plan->n_tiles > 0) {
+        e = adt::launch_redo(a, write_w, hs);
+        if (e != hipSuccess) return fail_hip(e, "redo launch");
+    }
+    return ADT_OK;
+}
+
+int awp_plan_read(awp_plan *plan, double *stats, int32_t *bits, int32_t *counter,
+                  uint8_t *bytes, int64_t *packed_size) {
+    if (!plan) return fail(ADT_EINVAL, "plan is null");
+    hipStream_t hs = plan->last_stream;
+    const size_t L = (size_t)plan->n_layers;
+    hipError_t e = hipSuccess;
+    auto get = [&](void *dst, const void *src, size_t bytes_) {
+        if (dst && bytes_ && e == hipSuccess)
+            e = hipMemcpyAsync(dst, src, bytes_, hipMemcpyDeviceToHost, hs);
+    };
+    get(stats, plan->stats, 24 * L);
+    get(bits, plan->bits, 4 * L);
+    get(counter, plan->counter, 4 * L);
+    get(bytes, plan->rbytes, L);
+    get(packed_size, plan->packed_size, 8);
+    if (e == hipSuccess) e = hipStreamSynchronize(hs);
+    if (e != hipSuccess) return fail_hip(e, "plan read");
+    return ADT_OK;
+}
+
+int awp_plan_destroy(awp_plan *plan) {
+    if (!plan) return ADT_OK;
+    if (plan->block) {
+        int saved = 0;
+        const bool have = hipGetDevice(&saved) == hipSuccess;
+        if (hipSetDevice(plan->device) == hipSuccess) (void)hipFree(plan->block);   // waits
+        if (have) (void)hipSetDevice(saved);
+    }
+    delete plan;
+    return ADT_OK;
+}
+
 const char *adt_strerror(int status) {
     switch (status) {
         case ADT_OK: return "success";
@@ -434,6 +637,9 @@ const char *adt_kernel_name(int kernel) {
         case adt::kKernelUnpack: return "unpack_kernel";
         case adt::kKernelStatsPartial: return "stats_partial_kernel";
         case adt::kKernelStatsFinal: return "stats_final_kernel";
+        case adt::kKernelFused: return "fused_kernel";
+        case adt::kKernelRule: return "rule_kernel";
+        case adt::kKernelRedo: return "redo_kernel";
         default: return "";
     }
 }

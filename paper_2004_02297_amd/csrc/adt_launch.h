@@ -17,7 +17,10 @@ enum KernelId {
     kKernelUnpack = 1,
     kKernelStatsPartial = 2,
     kKernelStatsFinal = 3,
-    kNumKernels = 4
+    kKernelFused = 4,
+    kKernelRule = 5,
+    kKernelRedo = 6,
+    kNumKernels = 7
 };
 
 // Defined in adt_api.hip.  True (and a fresh event pair, owned by the timing

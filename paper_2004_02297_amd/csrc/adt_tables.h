@@ -73,4 +73,38 @@ struct StatsFinalArgs {
     uint32_t inl_tile_off[kInlineLayers + 1];
 };
 
+// Device-resident tables of a plan (see awp_fused.hip): everything is a
+// device pointer; tile_off counts block tiles of kBlockTile weights.
+struct FusedArgs {
+    const uint32_t *weights;
+    uint8_t *packed;
+    uint32_t *weights_out;      // may be null when the truncated copy is not wanted
+    const int64_t *elem_off;
+    const int64_t *pack_off;
+    const uint32_t *tile_off;
+    const uint8_t *rbytes;
+    double *partial_sumsq;      // one per block tile
+    uint32_t *partial_absmax;
+    const int32_t *changed;
+    int n_layers;
+    uint32_t n_tiles;
+};
+
+struct RuleArgs {
+    const double *stats;        // n_layers x 3, written by the final kernel
+    double *l2_prev;
+    int32_t *bits;
+    int32_t *counter;
+    uint8_t *rbytes;
+    const int64_t *elem_off;
+    int64_t *pack_off;
+    int32_t *changed;
+    int64_t *packed_size;
+    int n_layers;
+    double T;
+    int interval;
+    int n_bits;
+    int is_first;
+};
+
 }  // namespace adt

@@ -1,0 +1,301 @@
+// Device-side building blocks shared by the ADT kernels (gfx950): cache-hinted
+// 128-bit accesses, the byte selection of Bitpack / Bitunpack (Section III,
+// Algorithms 2 and 5 of arXiv 2004.02297) on four weights at a time, and the
+// wave-tile movers that stage the byte stream through a wave-private LDS slice.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "adt_tables.h"
+
+namespace adt {
+
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));   // FP32 side: dword aligned
+
+// Cache hints.  FP32 weights are read once by pack and written once by unpack,
+// and the stream is read once by unpack: those accesses carry the nontemporal
+// hint, so their lines are not kept in L2 / Infinity Cache (on MI355X this
+// raises the sustained read rate by about 10 %).  The stream is WRITTEN with
+// ordinary stores: the consumer that follows (unpack, or a copy engine sending
+// it to a peer) then finds the most recent part of it in the Infinity Cache.
+// Measured on the statistics -> pack -> unpack pass over 138 M weights at
+// 2 bytes: 392 us without hints, 367 us with all four hints, 343 us with this
+// choice.
+#ifndef ADT_NT_FP32_LOAD
+#define ADT_NT_FP32_LOAD 1
+#endif
+#ifndef ADT_NT_FP32_STORE
+#define ADT_NT_FP32_STORE 1
+#endif
+#ifndef ADT_NT_STREAM_LOAD
+#define ADT_NT_STREAM_LOAD 1
+#endif
+#ifndef ADT_NT_STREAM_STORE
+#define ADT_NT_STREAM_STORE 0
+#endif
+__device__ __forceinline__ u32x4 load_fp32x4(const uint32_t *p) {
+    if (ADT_NT_FP32_LOAD) return __builtin_nontemporal_load((const u32x4_a4 *)p);
+    return *(const u32x4_a4 *)p;
+}
+__device__ __forceinline__ void store_fp32x4(uint32_t *p, const u32x4 v) {
+    if (ADT_NT_FP32_STORE) __builtin_nontemporal_store(v, (u32x4_a4 *)p);
+    else *(u32x4_a4 *)p = v;
+}
+__device__ __forceinline__ u32x4 load_stream16(const uint8_t *p) {   // 16-byte aligned
+    if (ADT_NT_STREAM_LOAD) return __builtin_nontemporal_load((const u32x4 *)p);
+    return *(const u32x4 *)p;
+}
+__device__ __forceinline__ void store_stream16(uint8_t *p, const u32x4 v) {
+    if (ADT_NT_STREAM_STORE) __builtin_nontemporal_store(v, (u32x4 *)p);
+    else *(u32x4 *)p = v;
+}
+
+constexpr int kPadDw = 8;                              // LDS pad before / after
+constexpr int kWaveLdsDw = kPadDw + kWaveTile + kPadDw;  // 1040 dwords per wave
+constexpr int kPadBytes = kPadDw * 4;
+
+__device__ __forceinline__ void wave_lds_sync() {
+    // LDS traffic of one wave is served in order; this only stops the
+    // compiler from moving accesses across the exchange point.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ({hi,lo} >> 8*sh) truncated to 32 bits, sh in 0..3.
+__device__ __forceinline__ uint32_t funnel(uint32_t hi, uint32_t lo, uint32_t sh) {
+    return (uint32_t)((((uint64_t)hi << 32) | lo) >> (8u * sh));
+}
+
+// Top R bytes of four words, as R dwords of stream (low kept byte first).
+template <int R>
+__device__ __forceinline__ void keep_top_bytes(const u32x4 u, uint32_t *d) {
+    if (R == 4) {
+        d[0] = u.x; d[1] = u.y; d[2] = u.z; d[3] = u.w;
+    } else if (R == 3) {
+        d[0] = (u.x >> 8) | ((u.y >> 8) << 24);
+        d[1] = (u.y >> 16) | ((u.z >> 8) << 16);
+        d[2] = (u.z >> 24) | ((u.w >> 8) << 8);
+    } else if (R == 2) {
+        d[0] = (u.x >> 16) | (u.y & 0xFFFF0000u);
+        d[1] = (u.z >> 16) | (u.w & 0xFFFF0000u);
+    } else {
+        d[0] = (u.x >> 24) | ((u.y >> 24) << 8) | ((u.z >> 24) << 16) |
+               (u.w & 0xFF000000u);
+    }
+}
+
+// Inverse: R dwords of stream -> four words with the low 8*(4-R) bits zero.
+template <int R>
+__device__ __forceinline__ u32x4 shift_to_top(const uint32_t *y) {
+    u32x4 u;
+    if (R == 4) {
+        u.x = y[0]; u.y = y[1]; u.z = y[2]; u.w = y[3];
+    } else if (R == 3) {
+        u.x = y[0] << 8;
+        u.y = ((y[0] >> 24) | (y[1] << 8)) << 8;
+        u.z = ((y[1] >> 16) | (y[2] << 16)) << 8;
+        u.w = y[2] & 0xFFFFFF00u;
+    } else if (R == 2) {
+        u.x = y[0] << 16;
+        u.y = y[0] & 0xFFFF0000u;
+        u.z = y[1] << 16;
+        u.w = y[1] & 0xFFFF0000u;
+    } else {
+        u.x = y[0] << 24;
+        u.y = (y[0] << 16) & 0xFF000000u;
+        u.z = (y[0] << 8) & 0xFF000000u;
+        u.w = y[0] & 0xFF000000u;
+    }
+    return u;
+}
+
+__device__ __forceinline__ uint32_t byte_of(const u32x4 v, int t) {
+    uint32_t w = (t < 8) ? ((t < 4) ? v.x : v.y) : ((t < 12) ? v.z : v.w);
+    return (w >> (8 * (t & 3))) & 0xFFu;
+}
+
+// ---------------------------------------------------------------------------
+// Load one wave tile: `len` (1..1024) FP32 words at src, four 128-bit loads per
+// lane; lane holds words 4c..4c+3 of the tile for c = j*64 + lane.  Words past
+// `len` read as zero.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void load_wave_tile(const uint32_t *__restrict__ src, int len,
+                                               int lane, u32x4 (&v)[kChunksPerLane]) {
+    if (len == kWaveTile) {
+#pragma unroll
+        for (int j = 0; j < kChunksPerLane; ++j)
+            v[j] = load_fp32x4(src + 4 * (j * kWave + lane));
+    } else {
+#pragma unroll
+        for (int j = 0; j < kChunksPerLane; ++j) {
+            const int e0 = 4 * (j * kWave + lane);
+            u32x4 t = {0u, 0u, 0u, 0u};
+            if (e0 + 4 <= len) {
+                t = load_fp32x4(src + e0);
+            } else {
+                if (e0 < len) t.x = src[e0];
+                if (e0 + 1 < len) t.y = src[e0 + 1];
+                if (e0 + 2 < len) t.z = src[e0 + 2];
+            }
+            v[j] = t;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Write the top R bytes of a loaded wave tile as len*R stream bytes at dst.
+// lds: this wave's slice (kWaveLdsDw dwords).
+// ---------------------------------------------------------------------------
+template <int R>
+__device__ __forceinline__ void stream_out_wave_tile(const u32x4 (&v)[kChunksPerLane],
+                                                     uint8_t *__restrict__ dst, int len,
+                                                     uint32_t *lds, int lane) {
+    uint32_t *body = lds + kPadDw;
+    const uint32_t s = (uint32_t)((uintptr_t)dst & 15u);   // wave uniform
+#pragma unroll
+    for (int j = 0; j < kChunksPerLane; ++j) {
+        uint32_t d[4];
+        keep_top_bytes<R>(v[j], d);
+        uint32_t *p = body + (j * kWave + lane) * R;
+#pragma unroll
+        for (int t = 0; t < R; ++t) p[t] = d[t];
+    }
+    wave_lds_sync();
+
+    if (len == kWaveTile && s == 0) {
+        // stream side 16-byte aligned: R full-width stores per lane
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            const int q = k * kWave + lane;
+            const u32x4 o = *(const u32x4 *)(body + 4 * q);
+            store_stream16(dst + 16 * q, o);
+        }
+        return;
+    }
+
+    // General case: walk the 16-byte grid of absolute stream addresses.
+    // Piece q covers tile-local stream bytes [16q - s, 16q - s + 16).
+    const int nbytes = len * R;
+    uint8_t *dst_al = dst - s;
+    const int npieces = (int)(s + nbytes + 15) >> 4;
+    const uint32_t sh = (0u - s) & 3u;
+    for (int k = 0; k * kWave < npieces; ++k) {
+        const int q = k * kWave + lane;
+        if (q < npieces) {
+            const int b0 = 16 * q - (int)s;
+            const int dw = (kPadBytes + b0) >> 2;          // >= 4, <= 1031
+            const uint32_t x0 = lds[dw], x1 = lds[dw + 1], x2 = lds[dw + 2],
+                           x3 = lds[dw + 3], x4 = lds[dw + 4];
+            u32x4 o;
+            o.x = funnel(x1, x0, sh);
+            o.y = funnel(x2, x1, sh);
+            o.z = funnel(x3, x2, sh);
+            o.w = funnel(x4, x3, sh);
+            if (b0 >= 0 && b0 + 16 <= nbytes) {
+                store_stream16(dst_al + 16 * q, o);
+            } else {
+                for (int t = 0; t < 16; ++t) {
+                    const int bt = b0 + t;
+                    if (bt >= 0 && bt < nbytes) dst_al[16 * q + t] = (uint8_t)byte_of(o, t);
+                }
+            }
+        }
+    }
+}
+
+// Pack one wave tile: `len` (1..1024) FP32 words at src -> len*R bytes at dst.
+template <int R>
+__device__ __forceinline__ void pack_wave_tile(const uint32_t *__restrict__ src,
+                                               uint8_t *__restrict__ dst, int len,
+                                               uint32_t *lds, int lane) {
+    u32x4 v[kChunksPerLane];
+    load_wave_tile(src, len, lane, v);
+    stream_out_wave_tile<R>(v, dst, len, lds, lane);
+}
+
+// ---------------------------------------------------------------------------
+// Unpack one wave tile: len*R stream bytes at src -> `len` FP32 words at dst.
+// [buf_lo, buf_hi) is the whole packed buffer: a 16-byte piece inside it may
+// be read whole even where it reaches into a neighbouring tile.
+// ---------------------------------------------------------------------------
+template <int R>
+__device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src,
+                                                 uint32_t *__restrict__ dst, int len,
+                                                 const uint8_t *buf_lo,
+                                                 const uint8_t *buf_hi, uint32_t *lds,
+                                                 int lane) {
+    const uint32_t s = (uint32_t)((uintptr_t)src & 15u);   // wave uniform
+    const bool full = (len == kWaveTile);
+
+    if (full && s == 0) {
+        u32x4 v[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k)
+            v[k] = load_stream16(src + 16 * (k * kWave + lane));
+#pragma unroll
+        for (int k = 0; k < R; ++k) *(u32x4 *)(lds + 4 * (k * kWave + lane)) = v[k];
+        wave_lds_sync();
+#pragma unroll
+        for (int j = 0; j < kChunksPerLane; ++j) {
+            const int c = j * kWave + lane;
+            uint32_t y[4];
+#pragma unroll
+            for (int t = 0; t < R; ++t) y[t] = lds[c * R + t];
+            store_fp32x4(dst + 4 * c, shift_to_top<R>(y));
+        }
+        return;
+    }
+
+    const int nbytes = len * R;
+    const uint8_t *src_al = src - s;
+    const int npieces = (int)(s + nbytes + 15) >> 4;       // <= 257
+    for (int k = 0; k * kWave < npieces; ++k) {
+        const int q = k * kWave + lane;
+        if (q < npieces) {
+            const uint8_t *a = src_al + 16 * q;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (a >= buf_lo && a + 16 <= buf_hi) {
+                v = load_stream16(a);
+            } else {
+                uint32_t w[4] = {0u, 0u, 0u, 0u};
+                for (int t = 0; t < 16; ++t)
+                    if (a + t >= buf_lo && a + t < buf_hi)
+                        w[t >> 2] |= (uint32_t)a[t] << (8 * (t & 3));
+                v.x = w[0]; v.y = w[1]; v.z = w[2]; v.w = w[3];
+            }
+            *(u32x4 *)(lds + 4 * q) = v;
+        }
+    }
+    wave_lds_sync();
+
+    // Stream byte b of the tile sits at LDS byte b + s.
+    const uint32_t sh = s & 3u;
+#pragma unroll
+    for (int j = 0; j < kChunksPerLane; ++j) {
+        const int c = j * kWave + lane;
+        const int e0 = 4 * c;
+        if (e0 < len) {
+            const int d = (int)(s + 4 * c * R) >> 2;        // <= 1023
+            uint32_t x[5];
+#pragma unroll
+            for (int t = 0; t <= R; ++t) x[t] = lds[d + t];
+            uint32_t y[4];
+#pragma unroll
+            for (int t = 0; t < R; ++t) y[t] = funnel(x[t + 1], x[t], sh);
+            const u32x4 u = shift_to_top<R>(y);
+            if (e0 + 4 <= len) {
+                store_fp32x4(dst + e0, u);
+            } else {
+                dst[e0] = u.x;
+                if (e0 + 1 < len) dst[e0 + 1] = u.y;
+                if (e0 + 2 < len) dst[e0 + 2] = u.z;
+            }
+        }
+    }
+}
+
+}  // namespace adt

@@ -1,0 +1,245 @@
+// One asynchronous pass of the whole path with device-resident AWP state
+// (gfx950): statistics -> AWP rule -> Bitpack -> Bitunpack of arXiv 2004.02297
+// (Section II / Algorithm 1, Section III / Algorithms 2 and 5) without a host
+// round trip and with the weights read from HBM once.
+//
+// The byte count of a layer changes at most a handful of times in a whole
+// training run (Algorithm 1 adds N bits after INTERVAL counted batches), so the
+// pass speculates that this batch keeps the previous batch's byte counts:
+//   1. fused kernel   : every wave tile of 1024 weights is loaded once; its
+//                       sum of squares and largest magnitude go to a per-block
+//                       partial, its top r bytes go to the packed stream and the
+//                       truncated words (what Bitunpack would return) go to the
+//                       output weights.
+//   2. final kernel   : per-layer reduction of the partials (fixed order).
+//   3. rule kernel    : one block runs Algorithm 1 on the fresh norms, rewrites
+//                       the byte counts and the stream offsets (prefix sum) and
+//                       raises `changed` if any byte count moved.
+//   4. redo kernel    : a small persistent grid that returns at once unless
+//                       `changed` is set; then it packs and truncates again with
+//                       the new table.
+// The result is what statistics -> rule -> pack -> unpack would give in that
+// order, whether or not the speculation held.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "adt_launch.h"
+#include "adt_tables.h"
+#include "adt_tile_ops.h"
+
+namespace adt {
+
+__device__ __forceinline__ double fused_wave_sum(double v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ uint32_t fused_wave_max(uint32_t v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)v, off, kWave);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+__device__ __forceinline__ void square_add(uint32_t bits, double &acc, uint32_t &mag) {
+    const double w = (double)__uint_as_float(bits);
+    acc = fma(w, w, acc);               // the square of a binary32 is exact in binary64
+    const uint32_t m = bits & 0x7FFFFFFFu;
+    mag = m > mag ? m : mag;            // NaN patterns order above infinity
+}
+
+// Truncated words of a loaded wave tile -> FP32 output (what unpack returns).
+template <int R>
+__device__ __forceinline__ void store_truncated(const u32x4 (&v)[kChunksPerLane],
+                                                uint32_t *__restrict__ dst, int len, int lane) {
+    const uint32_t mask = R == 4 ? 0xFFFFFFFFu : (0xFFFFFFFFu << (8 * (4 - R)));
+#pragma unroll
+    for (int j = 0; j < kChunksPerLane; ++j) {
+        const int e0 = 4 * (j * kWave + lane);
+        const u32x4 u = v[j] & mask;
+        if (e0 + 4 <= len) {
+            store_fp32x4(dst + e0, u);
+        } else {
+            if (e0 < len) dst[e0] = u.x;
+            if (e0 + 1 < len) dst[e0 + 1] = u.y;
+            if (e0 + 2 < len) dst[e0 + 2] = u.z;
+        }
+    }
+}
+
+template <int R, bool STATS, bool WRITE_W>
+__device__ __forceinline__ void fused_wave_tile(const uint32_t *__restrict__ src,
+                                                uint8_t *__restrict__ stream,
+                                                uint32_t *__restrict__ wout, int len,
+                                                uint32_t *lds, int lane, double &sum,
+                                                uint32_t &mag) {
+    u32x4 v[kChunksPerLane];
+    load_wave_tile(src, len, lane, v);
+    if (STATS) {
+        double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+#pragma unroll
+        for (int j = 0; j < kChunksPerLane; ++j) {   // words past len are zero
+            square_add(v[j].x, a0, mag);
+            square_add(v[j].y, a1, mag);
+            square_add(v[j].z, a2, mag);
+            square_add(v[j].w, a3, mag);
+        }
+        sum = (a0 + a1) + (a2 + a3);
+    }
+    if (WRITE_W) store_truncated<R>(v, wout, len, lane);
+    stream_out_wave_tile<R>(v, stream, len, lds, lane);
+}
+
+template <bool STATS, bool WRITE_W>
+__device__ __forceinline__ void fused_block_tile(const FusedArgs &a, uint32_t tile, int wave,
+                                                 int lane, uint32_t *lds, double &sum,
+                                                 uint32_t &mag) {
+    int lo = 0, hi = a.n_layers;            // largest lo with tile_off[lo] <= tile
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (a.tile_off[mid] <= tile) lo = mid; else hi = mid;
+    }
+    const int64_t e_begin = a.elem_off[lo];
+    const int64_t first = (int64_t)(tile - a.tile_off[lo]) * kBlockTile + (int64_t)wave * kWaveTile;
+    const int64_t left = (a.elem_off[lo + 1] - e_begin) - first;
+    const int len = __builtin_amdgcn_readfirstlane(
+        left <= 0 ? 0 : (left < kWaveTile ? (int)left : kWaveTile));
+    if (len == 0) return;
+    const int r = __builtin_amdgcn_readfirstlane((int)a.rbytes[lo]);
+    const uint32_t *src = a.weights + e_begin + first;
+    uint8_t *stream = a.packed + a.pack_off[lo] + first * r;
+    uint32_t *wout = WRITE_W ? a.weights_out + e_begin + first : nullptr;
+    switch (r) {
+        case 1: fused_wave_tile<1, STATS, WRITE_W>(src, stream, wout, len, lds, lane, sum, mag); break;
+        case 2: fused_wave_tile<2, STATS, WRITE_W>(src, stream, wout, len, lds, lane, sum, mag); break;
+        case 3: fused_wave_tile<3, STATS, WRITE_W>(src, stream, wout, len, lds, lane, sum, mag); break;
+        default: fused_wave_tile<4, STATS, WRITE_W>(src, stream, wout, len, lds, lane, sum, mag); break;
+    }
+}
+
+// Speculative pass: one block tile (4096 weights) per block, statistics on.
+template <bool WRITE_W>
+__global__ __launch_bounds__(kBlock) void fused_kernel(const FusedArgs a) {
+    __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
+    __shared__ double wsum[kWavesPerBlock];
+    __shared__ uint32_t wmag[kWavesPerBlock];
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    double sum = 0.0;
+    uint32_t mag = 0u;
+    fused_block_tile<true, WRITE_W>(a, blockIdx.x, wave, lane, smem[wave], sum, mag);
+    sum = fused_wave_sum(sum);
+    mag = fused_wave_max(mag);
+    if (lane == 0) {
+        wsum[wave] = sum;
+        wmag[wave] = mag;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        a.partial_sumsq[blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+        uint32_t m = wmag[0];
+#pragma unroll
+        for (int i = 1; i < kWavesPerBlock; ++i) m = wmag[i] > m ? wmag[i] : m;
+        a.partial_absmax[blockIdx.x] = m;
+    }
+}
+
+// Redo pass: persistent grid; does nothing unless the rule changed a byte count.
+template <bool WRITE_W>
+__global__ __launch_bounds__(kBlock) void redo_kernel(const FusedArgs a) {
+    __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
+    if (*a.changed == 0) return;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
+        double sum = 0.0;
+        uint32_t mag = 0u;
+        fused_block_tile<false, WRITE_W>(a, tile, wave, lane, smem[wave], sum, mag);
+        wave_lds_sync();     // the slice is reused by the next tile
+    }
+}
+
+// Algorithm 1 for all layers, then the stream offsets of the new byte counts.
+constexpr int kRuleBlock = 1024;
+constexpr int kRuleWaves = kRuleBlock / kWave;
+
+__global__ __launch_bounds__(kRuleBlock) void rule_kernel(const RuleArgs a) {
+    __shared__ int any_changed;
+    __shared__ long long carry;
+    __shared__ long long wave_total[kRuleWaves];
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) {
+        any_changed = 0;
+        carry = 0;
+    }
+    __syncthreads();
+    for (int base = 0; base < a.n_layers; base += kRuleBlock) {
+        const int l = base + tid;
+        long long size = 0;
+        if (l < a.n_layers) {
+            const double now = a.stats[3 * l + 1];
+            int bits = a.bits[l];
+            if (!a.is_first) {
+                const double prev = a.l2_prev[l];
+                const double delta =
+                    prev == 0.0 ? (now == 0.0 ? 0.0 : __builtin_huge_val()) : (now - prev) / prev;
+                int counter = a.counter[l];
+                if (delta < a.T) ++counter;
+                if (counter == a.interval) {
+                    bits += a.n_bits;
+                    if (bits > 32) bits = 32;
+                    counter = 0;
+                }
+                a.counter[l] = counter;
+                a.bits[l] = bits;
+            }
+            a.l2_prev[l] = now;
+            const int r = (bits + 7) >> 3;
+            if (r != (int)a.rbytes[l]) {
+                a.rbytes[l] = (uint8_t)r;
+                any_changed = 1;      // benign race: every writer stores 1
+            }
+            size = (long long)(a.elem_off[l + 1] - a.elem_off[l]) * r;
+        }
+        // exclusive prefix sum of `size` over the block, on top of `carry`
+        long long incl = size;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const long long o = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += o;
+        }
+        if (lane == kWave - 1) wave_total[wave] = incl;
+        __syncthreads();
+        long long before = carry;
+        for (int w = 0; w < wave; ++w) before += wave_total[w];
+        if (l < a.n_layers) a.pack_off[l] = before + incl - size;
+        __syncthreads();
+        if (tid == kRuleBlock - 1) carry = before + incl;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        a.pack_off[a.n_layers] = carry;
+        *a.packed_size = carry;
+        *a.changed = any_changed;
+    }
+}
+
+hipError_t launch_fused(const FusedArgs &a, bool write_w, hipStream_t stream) {
+    return write_w ? launch(fused_kernel<true>, kKernelFused, a.n_tiles, kBlock, stream, a)
+                   : launch(fused_kernel<false>, kKernelFused, a.n_tiles, kBlock, stream, a);
+}
+
+hipError_t launch_redo(const FusedArgs &a, bool write_w, hipStream_t stream) {
+    const uint32_t grid = a.n_tiles < 2048u ? a.n_tiles : 2048u;
+    return write_w ? launch(redo_kernel<true>, kKernelRedo, grid, kBlock, stream, a)
+                   : launch(redo_kernel<false>, kKernelRedo, grid, kBlock, stream, a);
+}
+
+hipError_t launch_rule(const RuleArgs &a, hipStream_t stream) {
+    return launch(rule_kernel, kKernelRule, 1u, kRuleBlock, stream, a);
+}
+
+}  // namespace adt

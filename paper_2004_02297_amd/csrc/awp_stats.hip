@@ -190,4 +190,11 @@ hipError_t launch_stats(const StatsArgs &a, const StatsFinalArgs &f, uint32_t n_
                                  (uint32_t)f.n_layers, kFinalBlock, stream, f);
 }
 
+hipError_t launch_stats_final(const StatsFinalArgs &f, bool inline_table, hipStream_t stream) {
+    return inline_table ? launch(stats_final_kernel<true>, kKernelStatsFinal, (uint32_t)f.n_layers,
+                                 kFinalBlock, stream, f)
+                        : launch(stats_final_kernel<false>, kKernelStatsFinal,
+                                 (uint32_t)f.n_layers, kFinalBlock, stream, f);
+}
+
 }  // namespace adt
