@@ -75,6 +75,66 @@ def plan_tiles(sizes) -> int:
     return int(np.sum((np.asarray(sizes) + 4095) // 4096))
 
 
+def run_ablation(args) -> int:
+    """Sustained time per call (back-to-back launches, HIP events around the
+    loop on the launch stream) of production vs ablation kernels."""
+    import torch
+
+    import paper_2004_02297_amd as adt
+    import workloads
+
+    adt.load_library()
+    iters = max(args.steps, 1)
+
+    def sustained_us(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / iters
+
+    out = {"mode": "ablation", "iters": iters, "unit": "us per call, back-to-back launches",
+           "hbm_peak_gbps": HBM_PEAK_GBPS, "cases": []}
+    for wl in ("vgg16_all2", "vgg16_all3", "resnet50"):
+        set_name, variant = WORKLOADS[wl]
+        ws = workloads.make_weight_set(set_name)
+        off = ws.layer_offsets
+        rb = workloads.config_bytes(set_name, variant)
+        nbytes = float(np.sum(np.diff(off) * (4 + rb.astype(np.int64))))
+        w = torch.from_numpy(ws.weights).cuda()
+        p = torch.empty(adt.adt_packed_size(off, rb), dtype=torch.uint8, device="cuda")
+        w2 = torch.empty_like(w)
+        rows = {
+            "pack: production (LDS repack, one launch)": lambda: adt.adt_pack(w, off, rb, out=p),
+            "pack: 128-bit loads, direct 4r-byte stores": lambda: adt.adt_ablation(
+                adt.ABLATION_VEC_DIRECT, False, w, off, rb, p),
+            "pack: naive, one weight per thread": lambda: adt.adt_ablation(
+                adt.ABLATION_NAIVE, False, w, off, rb, p),
+            "pack: production kernel, one launch per layer": lambda: adt.adt_ablation(
+                adt.ABLATION_PER_LAYER, False, w, off, rb, p),
+            "unpack: production (LDS repack, one launch)": lambda: adt.adt_unpack(p, off, rb, out=w2),
+            "unpack: naive, one weight per thread": lambda: adt.adt_ablation(
+                adt.ABLATION_NAIVE, True, w2, off, rb, p),
+            "unpack: production kernel, one launch per layer": lambda: adt.adt_ablation(
+                adt.ABLATION_PER_LAYER, True, w2, off, rb, p),
+        }
+        case = {"workload": wl, "n_layers": int(ws.n_layers), "n_weights": int(ws.n_weights),
+                "algorithmic_bytes": nbytes, "rows": {}}
+        for name, fn in rows.items():
+            us = sustained_us(fn)
+            case["rows"][name] = {"us": round(us, 1), "gbps": round(nbytes / us / 1e3, 1),
+                                  "hbm_frac": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)}
+        out["cases"].append(case)
+        del w, p, w2
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -91,7 +151,13 @@ def main() -> int:
                     help="after the timed regions, run one plain device copy of the weight "
                          "buffer (4N bytes read, 4N written): the known-size kernel that "
                          "rocprofv3 counter runs are scaled by")
+    ap.add_argument("--ablation", action="store_true",
+                    help="instead of the benchmark line, time the ablation variants (naive "
+                         "per-weight kernels, direct narrow stores, one launch per layer) "
+                         "against the production kernels and print one JSON line")
     args = ap.parse_args()
+    if args.ablation:
+        return run_ablation(args)
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no multi-GPU "
               "path); run with --gpus 1", file=sys.stderr)

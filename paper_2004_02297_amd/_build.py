@@ -8,7 +8,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadt.so")
-SOURCES = ["adt_api.hip", "adt_pack_unpack.hip", "awp_stats.hip", "awp_fused.hip"]
+SOURCES = ["adt_api.hip", "adt_pack_unpack.hip", "awp_stats.hip", "awp_fused.hip",
+           "adt_ablation.hip"]
 HEADERS = ["adt_tables.h", "adt_launch.h", "adt_tile_ops.h", os.path.join("..", "..", "include", "adt.h")]
 
 HIPCC_FLAGS = [

@@ -71,6 +71,8 @@ def load_library():
     lib.awp_plan_read.argtypes = [P, P, P, P, P, P]
     lib.awp_plan_destroy.restype = I
     lib.awp_plan_destroy.argtypes = [P]
+    lib.adt_ablation.restype = I
+    lib.adt_ablation.argtypes = [I, I, P, P, P, I, P, P]
     lib.adt_shutdown.restype = I
     lib.adt_shutdown.argtypes = []
     _lib = lib
@@ -278,3 +280,22 @@ class AwpPlan:
             self.close()
         except Exception:
             pass
+
+
+ABLATION_NAIVE, ABLATION_VEC_DIRECT, ABLATION_PER_LAYER = 1, 2, 3
+
+
+def adt_ablation(variant: int, unpack: bool, weights, layer_offsets, bytes_per_layer, packed,
+                 stream=None) -> None:
+    """adt_ablation: measurement variants of pack (weights -> packed) or, with
+    unpack=True, of unpack (packed -> weights)."""
+    import torch
+    off = _host(layer_offsets, np.int64)
+    rb = _host(bytes_per_layer, np.uint8)
+    w = _dev_tensor(weights, torch.float32, "weights")
+    p = _dev_tensor(packed, torch.uint8, "packed")
+    if w.numel() != int(off[-1]) or p.numel() < adt_packed_size(off, rb):
+        raise ValueError("buffer sizes do not match the tables")
+    _check(load_library().adt_ablation(int(variant), 1 if unpack else 0, w.data_ptr() or None,
+                                       _hptr(off), _hptr(rb), off.size - 1,
+                                       p.data_ptr() or None, _stream(stream)))

@@ -28,6 +28,7 @@ hipError_t launch_stats_final(const StatsFinalArgs &f, bool inline_table, hipStr
 hipError_t launch_fused(const FusedArgs &a, bool write_w, hipStream_t stream);
 hipError_t launch_redo(const FusedArgs &a, bool write_w, hipStream_t stream);
 hipError_t launch_rule(const RuleArgs &a, hipStream_t stream);
+hipError_t launch_ablation(int which, const AblationArgs &a, uint32_t n_tiles, hipStream_t s);
 }  // namespace adt
 
 // A plan: device-resident tables + AWP state (see include/adt.h).
@@ -577,6 +578,59 @@ int awp_plan_destroy(awp_plan *plan) {
         if (have) (void)hipSetDevice(saved);
     }
     delete plan;
+    return ADT_OK;
+}
+
+int adt_ablation(int variant, int unpack, const float *weights, const int64_t *layer_offsets,
+                 const uint8_t *bytes_per_layer, int n_layers, uint8_t *packed,
+                 adt_stream_t stream) {
+    int rc = check_tables(layer_offsets, bytes_per_layer, true, n_layers);
+    if (rc) return rc;
+    const int64_t n = n_layers ? layer_offsets[n_layers] : 0;
+    if (n_layers == 0 || n == 0) return ADT_OK;
+    if (!weights || !packed) return fail(ADT_EINVAL, "null device pointer");
+    if ((uintptr_t)weights & 3u) return fail(ADT_EALIGN, "FP32 buffer is not 4-byte aligned");
+    hipStream_t hs = (hipStream_t)stream;
+
+    if (variant == ADT_ABLATION_PER_LAYER) {
+        int64_t p = 0;
+        for (int l = 0; l < n_layers; ++l) {
+            const int64_t two[2] = {0, layer_offsets[l + 1] - layer_offsets[l]};
+            rc = pack_or_unpack(unpack ? kUnpack : kPack, weights + layer_offsets[l], two,
+                                bytes_per_layer + l, 1, packed + p, stream);
+            if (rc) return rc;
+            p += two[1] * (int64_t)bytes_per_layer[l];
+        }
+        return ADT_OK;
+    }
+    if (variant != ADT_ABLATION_NAIVE && variant != ADT_ABLATION_VEC_DIRECT)
+        return fail(ADT_EINVAL, "unknown ablation variant");
+    if (variant == ADT_ABLATION_VEC_DIRECT && unpack)
+        return fail(ADT_EINVAL, "the direct-store variant exists for pack only");
+    if (n_layers > adt::kInlineLayers) return fail(ADT_ERANGE, "ablation kernels take <= 128 layers");
+
+    adt::AblationArgs a;
+    a.weights = (const uint32_t *)weights;
+    a.packed = packed;
+    a.n_layers = n_layers;
+    const int64_t tile = variant == ADT_ABLATION_NAIVE ? adt::kNaiveTile : adt::kVecTile;
+    int64_t p = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        a.elem_off[l] = layer_offsets[l];
+        a.pack_off[l] = p;
+        a.rbytes[l] = bytes_per_layer[l];
+        if (variant == ADT_ABLATION_VEC_DIRECT &&
+            ((((uintptr_t)packed + (uintptr_t)p) & 3u) || (layer_offsets[l] & 3)))
+            return fail(ADT_EALIGN, "direct-store variant needs 4-byte aligned layer starts");
+        p += (layer_offsets[l + 1] - layer_offsets[l]) * (int64_t)bytes_per_layer[l];
+    }
+    a.elem_off[n_layers] = layer_offsets[n_layers];
+    a.pack_off[n_layers] = p;
+    rc = build_tile_off(layer_offsets, n_layers, tile, a.tile_off);
+    if (rc) return rc;
+    const int which = variant == ADT_ABLATION_NAIVE ? (unpack ? 1 : 0) : 2;
+    hipError_t e = adt::launch_ablation(which, a, a.tile_off[n_layers], hs);
+    if (e != hipSuccess) return fail_hip(e, "ablation launch");
     return ADT_OK;
 }
 

@@ -73,6 +73,19 @@ struct StatsFinalArgs {
     uint32_t inl_tile_off[kInlineLayers + 1];
 };
 
+// Ablation kernels (adt_ablation.hip): inline tables only.
+constexpr int kNaiveTile = kBlock;        // one weight per thread
+constexpr int kVecTile = kBlock * 4;      // four weights per thread
+struct AblationArgs {
+    const uint32_t *weights;
+    uint8_t *packed;
+    int n_layers;
+    int64_t elem_off[kInlineLayers + 1];
+    int64_t pack_off[kInlineLayers + 1];
+    uint32_t tile_off[kInlineLayers + 1];   // tiles of kNaiveTile / kVecTile weights
+    uint8_t rbytes[kInlineLayers];
+};
+
 // Device-resident tables of a plan (see awp_fused.hip): everything is a
 // device pointer; tile_off counts block tiles of kBlockTile weights.
 struct FusedArgs {

@@ -249,3 +249,31 @@ def test_non_default_stream(adt):
                           oracle.unpack(exp, ws.layer_offsets, rb).view(np.int32))
     np.testing.assert_allclose(st.cpu().numpy(), oracle.stats(ws.weights, ws.layer_offsets),
                                rtol=STATS_RTOL)
+
+
+# ------------------------------------------------------------------ ablation variants
+@pytest.mark.parametrize("variant", ["naive", "vec_direct", "per_layer"])
+def test_ablation_variants_give_the_same_bytes(adt, variant):
+    v = {"naive": adt.ABLATION_NAIVE, "vec_direct": adt.ABLATION_VEC_DIRECT,
+         "per_layer": adt.ABLATION_PER_LAYER}[variant]
+    if variant == "vec_direct":       # needs 4-byte aligned layer starts
+        sizes = [16, 4096, 4100, 8, 0, 20000, 12, 1028, 4]
+        off, rb, w = workloads.ragged_case(sizes, [1, 2, 3, 4, 1, 3, 1, 2, 3], seed=31)
+        w = np.concatenate([w, np.zeros(3, np.float32)])
+        off = off.copy(); off[-1] += 3                 # ragged tail inside the last layer
+    elif variant == "naive":          # at most 128 layers
+        sizes = [1, 0, 2, 3, 5, 15, 17, 255, 256, 257, 4095, 4097, 1023, 7, 9000, 31, 33, 1, 1, 12289]
+        off, rb, w = workloads.ragged_case(sizes, [1, 3, 1, 3, 2, 4, 1, 2, 3, 4] * 2, seed=32)
+    else:
+        off, rb, w = workloads.alignment_sweep_case()
+    exp = oracle.pack(w, off, rb)
+    dw = dev(w)
+    p = torch.full((exp.size + 32,), 0xA5, dtype=torch.uint8, device="cuda")
+    adt.adt_ablation(v, False, dw, off, rb, p[:exp.size] if exp.size else p)
+    got = p.cpu().numpy()
+    assert np.array_equal(got[:exp.size], exp) and np.all(got[exp.size:] == 0xA5)
+    if variant != "vec_direct":
+        back = torch.zeros_like(dw)
+        adt.adt_ablation(v, True, back, off, rb, p)
+        assert np.array_equal(back.view(torch.int32).cpu().numpy(),
+                              oracle.unpack(exp, off, rb).view(np.int32))
