@@ -92,6 +92,18 @@ int adt_unpack(const uint8_t *packed, const int64_t *layer_offsets,
                float *weights_out, adt_stream_t stream);
 
 /*
+ * adt_pack and adt_unpack of the same weights in one kernel: the weights are
+ * read once; `out` receives the packed stream exactly as adt_pack writes it
+ * and `weights_out` the FP32 words adt_unpack would return from that stream
+ * (bits(w) & (0xFFFFFFFF << 8*(4-r))).  For the device that packs for its
+ * peers and also needs the truncated weights itself.
+ *   weights_out  device, N floats, 4-byte aligned; must not overlap the others
+ */
+int adt_pack_unpack(const float *weights, const int64_t *layer_offsets,
+                    const uint8_t *bytes_per_layer, int n_layers, uint8_t *out,
+                    float *weights_out, adt_stream_t stream);
+
+/*
  * Per-layer statistics AWP monitors (Section II: the l2-norm of all weights
  * of a layer, every batch, on the full-precision weights).
  *   stats_out  device, n_layers * AWP_NSTATS doubles, row l =
@@ -158,6 +170,32 @@ int awp_plan_read(awp_plan *plan, double *stats, int32_t *bits, int32_t *counter
                   uint8_t *bytes, int64_t *packed_size);
 int awp_plan_destroy(awp_plan *plan);
 
+/*
+ * Layer groups.  Section IV-B: for ResNet the paper adapts the precision per
+ * building block instead of per layer.  A group is a run of consecutive layers
+ * [group_offsets[g], group_offsets[g+1]) (host array, n_groups + 1 entries,
+ * group_offsets[0] == 0, non-decreasing, last entry == n_layers) that shares
+ * one norm, the l2-norm over all weights of its layers, one AWP state and one
+ * byte count.
+ *   awp_group_norms         host only: l2_group[g] = sqrt(sum over the group's
+ *                           layers of stats[l][AWP_STAT_SUMSQ]), layers added
+ *                           in index order; feed it to awp_update with
+ *                           n_groups in place of n_layers
+ *   awp_expand_group_bytes  host only: bytes_layer[l] = bytes_group[g(l)]
+ *   awp_plan_create_grouped as awp_plan_create with groups; init_bits has
+ *                           n_groups entries (or NULL), and awp_plan_read
+ *                           returns n_groups entries of bits / counter while
+ *                           stats and bytes stay per layer
+ */
+int awp_group_norms(const double *stats, const int32_t *group_offsets, int n_groups,
+                    double *l2_group);
+int awp_expand_group_bytes(const uint8_t *bytes_group, const int32_t *group_offsets,
+                           int n_groups, uint8_t *bytes_layer);
+int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
+                            const int32_t *group_offsets, int n_groups,
+                            const int32_t *init_bits, double T, int interval, int n_bits,
+                            awp_plan **plan_out);
+
 /* Text for a status code (static string). */
 const char *adt_strerror(int status);
 
@@ -174,7 +212,7 @@ const char *adt_last_error(void);
  * ADT_NKERNELS entries, indexed as adt_kernel_name names them) and forgets
  * them.
  */
-#define ADT_NKERNELS 7
+#define ADT_NKERNELS 8
 typedef struct adt_kernel_time {
     int64_t launches;
     double total_ms;

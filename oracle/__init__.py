@@ -47,6 +47,8 @@ def _load():
         lib.oracle_unpack.argtypes = [P, P, P, ctypes.c_int, P]
         lib.oracle_stats.restype = None
         lib.oracle_stats.argtypes = [P, P, ctypes.c_int, P]
+        lib.oracle_group_norms.restype = None
+        lib.oracle_group_norms.argtypes = [P, P, P, ctypes.c_int, P]
         lib.oracle_awp_update.restype = None
         lib.oracle_awp_update.argtypes = [P, P, P, P, P, ctypes.c_int,
                                           ctypes.c_double, ctypes.c_int,
@@ -111,6 +113,18 @@ def stats(weights: np.ndarray, layer_offsets) -> np.ndarray:
         raise ValueError("weights size does not match layer_offsets[-1]")
     out = np.empty((L, NSTATS), dtype=np.float64)
     _load().oracle_stats(_ptr(w), _ptr(off), L, _ptr(out))
+    return out
+
+
+def group_norms(weights: np.ndarray, layer_offsets, group_offsets) -> np.ndarray:
+    """float64[G]: l2-norm over all weights of each run of layers."""
+    off, _, L = _tables(layer_offsets)
+    grp = np.ascontiguousarray(group_offsets, dtype=np.int32)
+    if grp[0] != 0 or grp[-1] != L or np.any(np.diff(grp) < 0):
+        raise ValueError("group_offsets must run from 0 to n_layers without decreasing")
+    w = np.ascontiguousarray(weights, dtype=np.float32)
+    out = np.empty(grp.size - 1, dtype=np.float64)
+    _load().oracle_group_norms(_ptr(w), _ptr(off), _ptr(grp), grp.size - 1, _ptr(out))
     return out
 
 

@@ -117,6 +117,27 @@ void oracle_stats(const float *W, const int64_t *layer_offsets, int n_layers,
 }
 
 /*
+ * Norms of layer groups (Section IV-B: for ResNet the precision is adapted per
+ * building block, not per layer).  Group g is the run of layers
+ * [group_offsets[g], group_offsets[g+1]); its norm is the l2-norm of all
+ * weights of those layers, squares accumulated in double in index order.
+ */
+void oracle_group_norms(const float *W, const int64_t *layer_offsets,
+                        const int32_t *group_offsets, int n_groups, double *l2_group)
+{
+    for (int g = 0; g < n_groups; ++g) {
+        double sumsq = 0.0;
+        int64_t first = layer_offsets[group_offsets[g]];
+        int64_t last = layer_offsets[group_offsets[g + 1]];
+        for (int64_t i = first; i < last; ++i) {
+            double w = (double)W[i];
+            sumsq += w * w;
+        }
+        l2_group[g] = sqrt(sumsq);
+    }
+}
+
+/*
  * One batch of the AWP rule for all layers (Section II, Algorithm 1).
  *
  * Per layer: delta = (|W_b| - |W_{b-1}|) / |W_{b-1}|; when delta < T the

@@ -14,7 +14,7 @@ import numpy as np
 from . import _build
 
 AWP_NSTATS = 3
-ADT_NKERNELS = 7
+ADT_NKERNELS = 8
 _lib = None
 
 
@@ -49,6 +49,8 @@ def load_library():
     lib.adt_pack.argtypes = [P, P, P, I, P, P]
     lib.adt_unpack.restype = I
     lib.adt_unpack.argtypes = [P, P, P, I, P, P]
+    lib.adt_pack_unpack.restype = I
+    lib.adt_pack_unpack.argtypes = [P, P, P, I, P, P, P]
     lib.awp_layer_stats.restype = I
     lib.awp_layer_stats.argtypes = [P, P, I, P, P]
     lib.awp_update.restype = I
@@ -65,6 +67,13 @@ def load_library():
     lib.adt_kernel_name.argtypes = [I]
     lib.awp_plan_create.restype = I
     lib.awp_plan_create.argtypes = [P, I, P, ctypes.c_double, I, I, ctypes.POINTER(P)]
+    lib.awp_plan_create_grouped.restype = I
+    lib.awp_plan_create_grouped.argtypes = [P, I, P, I, P, ctypes.c_double, I, I,
+                                            ctypes.POINTER(P)]
+    lib.awp_group_norms.restype = I
+    lib.awp_group_norms.argtypes = [P, P, I, P]
+    lib.awp_expand_group_bytes.restype = I
+    lib.awp_expand_group_bytes.argtypes = [P, P, I, P]
     lib.awp_adt_step.restype = I
     lib.awp_adt_step.argtypes = [P, P, P, I64, P, P]
     lib.awp_plan_read.restype = I
@@ -166,6 +175,33 @@ def adt_unpack(packed, layer_offsets, bytes_per_layer, out=None, stream=None):
     return out
 
 
+def adt_pack_unpack(weights, layer_offsets, bytes_per_layer, out=None, weights_out=None,
+                    stream=None):
+    """adt_pack_unpack: one kernel; returns (packed stream, truncated FP32 weights)."""
+    import torch
+    off = _host(layer_offsets, np.int64)
+    rb = _host(bytes_per_layer, np.uint8)
+    L = off.size - 1
+    if rb.size != L:
+        raise ValueError("bytes_per_layer must have n_layers entries")
+    w = _dev_tensor(weights, torch.float32, "weights")
+    size = adt_packed_size(off, rb)
+    if w.numel() != int(off[-1]):
+        raise ValueError("weights size does not match layer_offsets[-1]")
+    if out is None:
+        out = torch.empty(size, dtype=torch.uint8, device=w.device)
+    elif _dev_tensor(out, torch.uint8, "out").numel() < size:
+        raise ValueError("out is smaller than the packed size")
+    if weights_out is None:
+        weights_out = torch.empty_like(w)
+    elif _dev_tensor(weights_out, torch.float32, "weights_out").numel() != w.numel():
+        raise ValueError("weights_out size does not match")
+    _check(load_library().adt_pack_unpack(w.data_ptr() or None, _hptr(off), _hptr(rb), L,
+                                          out.data_ptr() or None,
+                                          weights_out.data_ptr() or None, _stream(stream)))
+    return out, weights_out
+
+
 def awp_layer_stats(weights, layer_offsets, out=None, stream=None):
     """awp_layer_stats: device float32[N] -> device float64[L, 3]."""
     import torch
@@ -230,17 +266,21 @@ class AwpPlan:
     statistics -> rule -> pack -> unpack (see include/adt.h)."""
 
     def __init__(self, layer_offsets, T: float, interval: int, n_bits: int = 8,
-                 init_bits=None):
+                 init_bits=None, group_offsets=None):
+        self._h = None
         self._lib = load_library()
         off = _host(layer_offsets, np.int64)
         self.n_layers = off.size - 1
         self.n_weights = int(off[-1])
+        grp = None if group_offsets is None else _host(group_offsets, np.int32)
+        self.n_groups = self.n_layers if grp is None else grp.size - 1
         ib = None if init_bits is None else _host(init_bits, np.int32)
-        if ib is not None and ib.shape != (self.n_layers,):
-            raise ValueError("init_bits must have n_layers entries")
+        if ib is not None and ib.shape != (self.n_groups,):
+            raise ValueError("init_bits must have one entry per group")
         h = ctypes.c_void_p()
-        _check(self._lib.awp_plan_create(_hptr(off), self.n_layers, _hptr(ib), float(T),
-                                         int(interval), int(n_bits), ctypes.byref(h)))
+        _check(self._lib.awp_plan_create_grouped(_hptr(off), self.n_layers, _hptr(grp),
+                                                 self.n_groups, _hptr(ib), float(T),
+                                                 int(interval), int(n_bits), ctypes.byref(h)))
         self._h = h
 
     def step(self, weights, packed, weights_out=None, stream=None) -> None:
@@ -261,9 +301,9 @@ class AwpPlan:
 
     def read(self) -> dict:
         """awp_plan_read: waits for the enqueued steps, returns the state."""
-        L = self.n_layers
+        L, G = self.n_layers, self.n_groups
         st = np.empty((L, AWP_NSTATS), np.float64)
-        bits, cnt = np.empty(L, np.int32), np.empty(L, np.int32)
+        bits, cnt = np.empty(G, np.int32), np.empty(G, np.int32)
         rb, size = np.empty(L, np.uint8), np.zeros(1, np.int64)
         _check(self._lib.awp_plan_read(self._h, _hptr(st), _hptr(bits), _hptr(cnt), _hptr(rb),
                                        _hptr(size)))
@@ -299,3 +339,21 @@ def adt_ablation(variant: int, unpack: bool, weights, layer_offsets, bytes_per_l
     _check(load_library().adt_ablation(int(variant), 1 if unpack else 0, w.data_ptr() or None,
                                        _hptr(off), _hptr(rb), off.size - 1,
                                        p.data_ptr() or None, _stream(stream)))
+
+
+def awp_group_norms(stats, group_offsets) -> np.ndarray:
+    """awp_group_norms: per-group l2-norms from per-layer statistics (host)."""
+    st = _host(stats, np.float64)
+    grp = _host(group_offsets, np.int32)
+    out = np.empty(grp.size - 1, np.float64)
+    _check(load_library().awp_group_norms(_hptr(st), _hptr(grp), grp.size - 1, _hptr(out)))
+    return out
+
+
+def awp_expand_group_bytes(bytes_group, group_offsets) -> np.ndarray:
+    """awp_expand_group_bytes: per-layer byte counts from per-group ones (host)."""
+    bg = _host(bytes_group, np.uint8)
+    grp = _host(group_offsets, np.int32)
+    out = np.empty(int(grp[-1]), np.uint8)
+    _check(load_library().awp_expand_group_bytes(_hptr(bg), _hptr(grp), grp.size - 1, _hptr(out)))
+    return out

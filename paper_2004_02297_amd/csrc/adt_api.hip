@@ -28,6 +28,8 @@ hipError_t launch_stats_final(const StatsFinalArgs &f, bool inline_table, hipStr
 hipError_t launch_fused(const FusedArgs &a, bool write_w, hipStream_t stream);
 hipError_t launch_redo(const FusedArgs &a, bool write_w, hipStream_t stream);
 hipError_t launch_rule(const RuleArgs &a, hipStream_t stream);
+hipError_t launch_pack_unpack(const PackUnpackArgs &a, uint32_t n_tiles, bool inline_table,
+                              hipStream_t stream);
 hipError_t launch_ablation(int which, const AblationArgs &a, uint32_t n_tiles, hipStream_t s);
 }  // namespace adt
 
@@ -35,6 +37,8 @@ hipError_t launch_ablation(int which, const AblationArgs &a, uint32_t n_tiles, h
 struct awp_plan {
     int device = 0;
     int n_layers = 0;
+    int n_groups = 0;
+    int32_t *group_off = nullptr;
     int64_t n = 0;
     uint32_t n_tiles = 0;
     double T = 0.0;
@@ -168,18 +172,49 @@ int build_tile_off(const int64_t *off, int n_layers, int64_t tile, uint32_t *til
     return ADT_OK;
 }
 
-enum Direction { kPack, kUnpack };
+// Groups are runs of consecutive layers; null means one group per layer.
+int check_groups(const int32_t *group_offsets, int n_groups, int n_layers,
+                 std::vector<int32_t> *out) {
+    if (n_groups < 0) return fail(ADT_EINVAL, "n_groups < 0");
+    if (!group_offsets) {
+        if (n_groups != n_layers)
+            return fail(ADT_EINVAL, "without group_offsets n_groups must equal n_layers");
+        if (out) {
+            out->resize((size_t)n_layers + 1);
+            for (int l = 0; l <= n_layers; ++l) (*out)[(size_t)l] = l;
+        }
+        return ADT_OK;
+    }
+    if (group_offsets[0] != 0) return fail(ADT_EINVAL, "group_offsets[0] != 0");
+    for (int g = 0; g < n_groups; ++g)
+        if (group_offsets[g + 1] < group_offsets[g])
+            return fail(ADT_EINVAL, "group_offsets decreases");
+    if (group_offsets[n_groups] != n_layers)
+        return fail(ADT_EINVAL, "group_offsets must end at n_layers");
+    if (out) out->assign(group_offsets, group_offsets + n_groups + 1);
+    return ADT_OK;
+}
+
+enum Direction { kPack, kUnpack, kPackUnpack };
 
 int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
-                   const uint8_t *rb, int n_layers, const void *packed, adt_stream_t stream) {
+                   const uint8_t *rb, int n_layers, const void *packed, adt_stream_t stream,
+                   void *weights_out = nullptr) {
     int rc = check_tables(off, rb, true, n_layers);
     if (rc) return rc;
     const int64_t n = n_layers ? off[n_layers] : 0;
     if (n_layers == 0 || n == 0) return ADT_OK;
     if (!weights || !packed) return fail(ADT_EINVAL, "null device pointer");
     if ((uintptr_t)weights & 3u) return fail(ADT_EALIGN, "FP32 buffer is not 4-byte aligned");
+    if (dir == kPackUnpack) {
+        if (!weights_out) return fail(ADT_EINVAL, "weights_out is null");
+        if ((uintptr_t)weights_out & 3u)
+            return fail(ADT_EALIGN, "FP32 buffer is not 4-byte aligned");
+    }
 
-    adt::PackArgs a;
+    adt::PackUnpackArgs pu;
+    pu.weights_out = (uint32_t *)weights_out;
+    adt::PackArgs &a = pu.p;
     a.weights = (const uint32_t *)weights;
     a.packed = (uint8_t *)packed;
     a.n_layers = n_layers;
@@ -236,14 +271,15 @@ int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
         hipError_t e = hipMemcpyAsync(slot->dev, slot->host, bytes, hipMemcpyHostToDevice, hs);
         if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(table)");
     }
-    hipError_t e = dir == kPack ? adt::launch_pack(a, n_tiles, inl, hs)
-                                : adt::launch_unpack(a, n_tiles, inl, hs);
+    hipError_t e = dir == kPack     ? adt::launch_pack(a, n_tiles, inl, hs)
+                   : dir == kUnpack ? adt::launch_unpack(a, n_tiles, inl, hs)
+                                    : adt::launch_pack_unpack(pu, n_tiles, inl, hs);
     if (!inl) {
         // guard the slot even if the launch failed: the copy may be in flight
         if (hipEventRecord(slot->ev, hs) == hipSuccess) slot->pending = true;
         else (void)hipStreamSynchronize(hs);
     }
-    if (e != hipSuccess) return fail_hip(e, dir == kPack ? "pack launch" : "unpack launch");
+    if (e != hipSuccess) return fail_hip(e, "pack / unpack launch");
     return ADT_OK;
 }
 
@@ -290,6 +326,13 @@ int adt_unpack(const uint8_t *packed, const int64_t *layer_offsets,
                adt_stream_t stream) {
     return pack_or_unpack(kUnpack, weights_out, layer_offsets, bytes_per_layer, n_layers,
                           packed, stream);
+}
+
+int adt_pack_unpack(const float *weights, const int64_t *layer_offsets,
+                    const uint8_t *bytes_per_layer, int n_layers, uint8_t *out,
+                    float *weights_out, adt_stream_t stream) {
+    return pack_or_unpack(kPackUnpack, weights, layer_offsets, bytes_per_layer, n_layers, out,
+                          stream, weights_out);
 }
 
 int awp_layer_stats(const float *weights, const int64_t *layer_offsets, int n_layers,
@@ -403,24 +446,38 @@ int awp_update(const double *l2_now, double *l2_prev, int32_t *counter, int32_t 
 
 int awp_plan_create(const int64_t *layer_offsets, int n_layers, const int32_t *init_bits,
                     double T, int interval, int n_bits, awp_plan **plan_out) {
+    return awp_plan_create_grouped(layer_offsets, n_layers, nullptr, n_layers, init_bits, T,
+                                   interval, n_bits, plan_out);
+}
+
+int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
+                            const int32_t *group_offsets, int n_groups,
+                            const int32_t *init_bits, double T, int interval, int n_bits,
+                            awp_plan **plan_out) {
     if (!plan_out) return fail(ADT_EINVAL, "plan_out is null");
     *plan_out = nullptr;
     int rc = check_tables(layer_offsets, nullptr, false, n_layers);
     if (rc) return rc;
     if (interval < 1 || n_bits < 0) return fail(ADT_EINVAL, "interval < 1 or n_bits < 0");
+    std::vector<int32_t> groups;
+    rc = check_groups(group_offsets, n_groups, n_layers, &groups);
+    if (rc) return rc;
+    const size_t G = (size_t)n_groups;
     const size_t L = (size_t)n_layers, L1 = L + 1;
     std::vector<uint32_t> tile_off(L1);
     rc = build_tile_off(layer_offsets, n_layers, adt::kBlockTile, tile_off.data());
     if (rc) return rc;
-    std::vector<int32_t> bits(L);
+    std::vector<int32_t> bits(G);
     std::vector<uint8_t> rb(L);
     std::vector<int64_t> pack_off(L1);
+    for (size_t g = 0; g < G; ++g) {
+        const int32_t b = init_bits ? init_bits[g] : 8;
+        if (b < 1 || b > 32) return fail(ADT_EINVAL, "init_bits not in 1..32");
+        bits[g] = b;
+        for (int32_t l = groups[g]; l < groups[g + 1]; ++l) rb[(size_t)l] = (uint8_t)((b + 7) >> 3);
+    }
     int64_t p = 0;
     for (size_t l = 0; l < L; ++l) {
-        const int32_t b = init_bits ? init_bits[l] : 8;
-        if (b < 1 || b > 32) return fail(ADT_EINVAL, "init_bits not in 1..32");
-        bits[l] = b;
-        rb[l] = (uint8_t)((b + 7) >> 3);
         pack_off[l] = p;
         p += (layer_offsets[l + 1] - layer_offsets[l]) * (int64_t)rb[l];
     }
@@ -431,6 +488,7 @@ int awp_plan_create(const int64_t *layer_offsets, int n_layers, const int32_t *i
     hipError_t e = hipGetDevice(&pl->device);
     if (e != hipSuccess) { delete pl; return fail_hip(e, "hipGetDevice"); }
     pl->n_layers = n_layers;
+    pl->n_groups = n_groups;
     pl->n = layer_offsets[n_layers];
     pl->n_tiles = tile_off[L];
     pl->T = T;
@@ -441,9 +499,10 @@ int awp_plan_create(const int64_t *layer_offsets, int n_layers, const int32_t *i
     size_t o = 0;
     auto take = [&o](size_t bytes) { size_t at = o; o += align8(bytes); return at; };
     const size_t o_elem = take(8 * L1), o_pack = take(8 * L1), o_psize = take(8);
-    const size_t o_prev = take(8 * L), o_stats = take(24 * L), o_psum = take(8 * (size_t)pl->n_tiles);
+    const size_t o_prev = take(8 * G), o_stats = take(24 * L), o_psum = take(8 * (size_t)pl->n_tiles);
     const size_t o_tile = take(4 * L1), o_pmax = take(4 * (size_t)pl->n_tiles);
-    const size_t o_bits = take(4 * L), o_cnt = take(4 * L), o_chg = take(4), o_rb = take(L);
+    const size_t o_bits = take(4 * G), o_cnt = take(4 * G), o_grp = take(4 * (G + 1));
+    const size_t o_chg = take(4), o_rb = take(L);
     const size_t total = o + 8;
     e = hipMalloc((void **)&pl->block, total);
     if (e != hipSuccess) { (void)hipGetLastError(); delete pl; return fail(ADT_ENOMEM, "plan tables"); }
@@ -458,6 +517,7 @@ int awp_plan_create(const int64_t *layer_offsets, int n_layers, const int32_t *i
     pl->partial_absmax = (uint32_t *)(b + o_pmax);
     pl->bits = (int32_t *)(b + o_bits);
     pl->counter = (int32_t *)(b + o_cnt);
+    pl->group_off = (int32_t *)(b + o_grp);
     pl->changed = (int32_t *)(b + o_chg);
     pl->rbytes = (uint8_t *)(b + o_rb);
 
@@ -466,7 +526,9 @@ int awp_plan_create(const int64_t *layer_offsets, int n_layers, const int32_t *i
     if (e == hipSuccess) e = hipMemcpy(pl->pack_off, pack_off.data(), 8 * L1, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(pl->packed_size, &p, 8, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(pl->tile_off, tile_off.data(), 4 * L1, hipMemcpyHostToDevice);
-    if (e == hipSuccess && L) e = hipMemcpy(pl->bits, bits.data(), 4 * L, hipMemcpyHostToDevice);
+    if (e == hipSuccess && G) e = hipMemcpy(pl->bits, bits.data(), 4 * G, hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = hipMemcpy(pl->group_off, groups.data(), 4 * (G + 1), hipMemcpyHostToDevice);
     if (e == hipSuccess && L) e = hipMemcpy(pl->rbytes, rb.data(), L, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
@@ -526,6 +588,8 @@ int awp_adt_step(awp_plan *plan, const float *weights, uint8_t *packed,
 
     adt::RuleArgs r;
     r.stats = plan->stats;
+    r.group_off = plan->group_off;
+    r.n_groups = plan->n_groups;
     r.l2_prev = plan->l2_prev;
     r.bits = plan->bits;
     r.counter = plan->counter;
@@ -560,8 +624,8 @@ int awp_plan_read(awp_plan *plan, double *stats, int32_t *bits, int32_t *counter
             e = hipMemcpyAsync(dst, src, bytes_, hipMemcpyDeviceToHost, hs);
     };
     get(stats, plan->stats, 24 * L);
-    get(bits, plan->bits, 4 * L);
-    get(counter, plan->counter, 4 * L);
+    get(bits, plan->bits, 4 * (size_t)plan->n_groups);
+    get(counter, plan->counter, 4 * (size_t)plan->n_groups);
     get(bytes, plan->rbytes, L);
     get(packed_size, plan->packed_size, 8);
     if (e == hipSuccess) e = hipStreamSynchronize(hs);
@@ -634,6 +698,33 @@ int adt_ablation(int variant, int unpack, const float *weights, const int64_t *l
     return ADT_OK;
 }
 
+int awp_group_norms(const double *stats, const int32_t *group_offsets, int n_groups,
+                    double *l2_group) {
+    if (n_groups < 0 || !group_offsets || (n_groups > 0 && (!stats || !l2_group)))
+        return fail(ADT_EINVAL, "null argument or n_groups < 0");
+    int rc = check_groups(group_offsets, n_groups, group_offsets[n_groups], nullptr);
+    if (rc) return rc;
+    for (int g = 0; g < n_groups; ++g) {
+        double sumsq = 0.0;
+        for (int32_t l = group_offsets[g]; l < group_offsets[g + 1]; ++l)
+            sumsq += stats[(size_t)l * AWP_NSTATS + AWP_STAT_SUMSQ];
+        l2_group[g] = sqrt(sumsq);
+    }
+    return ADT_OK;
+}
+
+int awp_expand_group_bytes(const uint8_t *bytes_group, const int32_t *group_offsets,
+                           int n_groups, uint8_t *bytes_layer) {
+    if (n_groups < 0 || !group_offsets || (n_groups > 0 && (!bytes_group || !bytes_layer)))
+        return fail(ADT_EINVAL, "null argument or n_groups < 0");
+    int rc = check_groups(group_offsets, n_groups, group_offsets[n_groups], nullptr);
+    if (rc) return rc;
+    for (int g = 0; g < n_groups; ++g)
+        for (int32_t l = group_offsets[g]; l < group_offsets[g + 1]; ++l)
+            bytes_layer[l] = bytes_group[g];
+    return ADT_OK;
+}
+
 const char *adt_strerror(int status) {
     switch (status) {
         case ADT_OK: return "success";
@@ -694,6 +785,7 @@ const char *adt_kernel_name(int kernel) {
         case adt::kKernelFused: return "fused_kernel";
         case adt::kKernelRule: return "rule_kernel";
         case adt::kKernelRedo: return "redo_kernel";
+        case adt::kKernelPackUnpack: return "pack_unpack_kernel";
         default: return "";
     }
 }

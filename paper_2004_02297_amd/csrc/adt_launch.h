@@ -20,7 +20,8 @@ enum KernelId {
     kKernelFused = 4,
     kKernelRule = 5,
     kKernelRedo = 6,
-    kNumKernels = 7
+    kKernelPackUnpack = 7,
+    kNumKernels = 8
 };
 
 // Defined in adt_api.hip.  True (and a fresh event pair, owned by the timing

@@ -31,37 +31,6 @@ namespace adt {
 // ---------------------------------------------------------------------------
 // Kernels: block -> (layer, tile) through the offset table, wave -> wave tile.
 // ---------------------------------------------------------------------------
-struct TileRef {
-    int64_t elem;      // first weight of the wave tile (absolute index)
-    int64_t byte;      // first stream byte of the wave tile
-    int len;           // weights in the wave tile, 0 = nothing to do
-    int r;
-};
-
-template <bool INLINE>
-__device__ __forceinline__ TileRef locate(const PackArgs &a, uint32_t block, int wave) {
-    const uint32_t *tile_off = INLINE ? a.inl.tile_off : a.dev.tile_off;
-    const int64_t *elem_off = INLINE ? a.inl.elem_off : a.dev.elem_off;
-    const int64_t *pack_off = INLINE ? a.inl.pack_off : a.dev.pack_off;
-    const uint8_t *rbytes = INLINE ? a.inl.rbytes : a.dev.rbytes;
-    int lo = 0, hi = a.n_layers;            // largest lo with tile_off[lo] <= block
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (tile_off[mid] <= block) lo = mid; else hi = mid;
-    }
-    const int64_t e_begin = elem_off[lo];
-    const int64_t n = elem_off[lo + 1] - e_begin;
-    const int64_t first = (int64_t)(block - tile_off[lo]) * kBlockTile +
-                          (int64_t)wave * kWaveTile;
-    TileRef t;
-    t.r = rbytes[lo];
-    t.elem = e_begin + first;
-    t.byte = pack_off[lo] + first * t.r;
-    const int64_t left = n - first;
-    t.len = left <= 0 ? 0 : (left < kWaveTile ? (int)left : kWaveTile);
-    return t;
-}
-
 template <bool INLINE>
 __global__ __launch_bounds__(kBlock) void pack_kernel(const PackArgs a) {
     __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];

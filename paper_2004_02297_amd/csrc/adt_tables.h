@@ -14,7 +14,10 @@ namespace adt {
 constexpr int kWave = 64;               // CDNA wavefront
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlock = kWave * kWavesPerBlock;
-constexpr int kChunksPerLane = 4;       // 128-bit loads in flight per lane
+#ifndef ADT_CHUNKS_PER_LANE
+#define ADT_CHUNKS_PER_LANE 4
+#endif
+constexpr int kChunksPerLane = ADT_CHUNKS_PER_LANE;   // 128-bit loads in flight per lane
 constexpr int kWaveTile = kWave * kChunksPerLane * 4;    // 1024 weights per wave
 constexpr int kBlockTile = kWaveTile * kWavesPerBlock;   // 4096 weights per block
 
@@ -47,6 +50,12 @@ struct PackArgs {
     int n_layers;
     DeviceTable dev;           // used when n_layers > kInlineLayers
     InlineTable inl;
+};
+
+// adt_pack_unpack: pack plus the truncated FP32 copy in one kernel.
+struct PackUnpackArgs {
+    PackArgs p;
+    uint32_t *weights_out;
 };
 
 struct StatsInlineTable {
@@ -105,9 +114,11 @@ struct FusedArgs {
 
 struct RuleArgs {
     const double *stats;        // n_layers x 3, written by the final kernel
-    double *l2_prev;
-    int32_t *bits;
-    int32_t *counter;
+    const int32_t *group_off;   // n_groups + 1 layer indices
+    int n_groups;
+    double *l2_prev;            // per group
+    int32_t *bits;              // per group
+    int32_t *counter;           // per group
     uint8_t *rbytes;
     const int64_t *elem_off;
     int64_t *pack_off;

@@ -169,7 +169,7 @@ __device__ __forceinline__ void stream_out_wave_tile(const u32x4 (&v)[kChunksPer
     if (len == kWaveTile && s == 0) {
         // stream side 16-byte aligned: R full-width stores per lane
 #pragma unroll
-        for (int k = 0; k < R; ++k) {
+        for (int k = 0; k < R * kChunksPerLane / 4; ++k) {
             const int q = k * kWave + lane;
             const u32x4 o = *(const u32x4 *)(body + 4 * q);
             store_stream16(dst + 16 * q, o);
@@ -187,7 +187,7 @@ __device__ __forceinline__ void stream_out_wave_tile(const u32x4 (&v)[kChunksPer
         const int q = k * kWave + lane;
         if (q < npieces) {
             const int b0 = 16 * q - (int)s;
-            const int dw = (kPadBytes + b0) >> 2;          // >= 4, <= 1031
+            const int dw = (kPadBytes + b0) >> 2;          // >= 4, <= kWaveTile + 7
             const uint32_t x0 = lds[dw], x1 = lds[dw + 1], x2 = lds[dw + 2],
                            x3 = lds[dw + 3], x4 = lds[dw + 4];
             u32x4 o;
@@ -232,12 +232,13 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
     const bool full = (len == kWaveTile);
 
     if (full && s == 0) {
-        u32x4 v[R];
+        constexpr int kPieces = R * kChunksPerLane / 4;     // 16-byte pieces per lane
+        u32x4 v[kPieces];
 #pragma unroll
-        for (int k = 0; k < R; ++k)
+        for (int k = 0; k < kPieces; ++k)
             v[k] = load_stream16(src + 16 * (k * kWave + lane));
 #pragma unroll
-        for (int k = 0; k < R; ++k) *(u32x4 *)(lds + 4 * (k * kWave + lane)) = v[k];
+        for (int k = 0; k < kPieces; ++k) *(u32x4 *)(lds + 4 * (k * kWave + lane)) = v[k];
         wave_lds_sync();
 #pragma unroll
         for (int j = 0; j < kChunksPerLane; ++j) {
@@ -252,7 +253,7 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
 
     const int nbytes = len * R;
     const uint8_t *src_al = src - s;
-    const int npieces = (int)(s + nbytes + 15) >> 4;       // <= 257
+    const int npieces = (int)(s + nbytes + 15) >> 4;       // <= kWaveTile / 4 + 1
     for (int k = 0; k * kWave < npieces; ++k) {
         const int q = k * kWave + lane;
         if (q < npieces) {
@@ -279,7 +280,7 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
         const int c = j * kWave + lane;
         const int e0 = 4 * c;
         if (e0 < len) {
-            const int d = (int)(s + 4 * c * R) >> 2;        // <= 1023
+            const int d = (int)(s + 4 * c * R) >> 2;        // <= kWaveTile - 1
             uint32_t x[5];
 #pragma unroll
             for (int t = 0; t <= R; ++t) x[t] = lds[d + t];
@@ -296,6 +297,40 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
             }
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// Block -> (layer, tile) through the offset table, wave -> wave tile.
+// ---------------------------------------------------------------------------
+struct TileRef {
+    int64_t elem;      // first weight of the wave tile (absolute index)
+    int64_t byte;      // first stream byte of the wave tile
+    int len;           // weights in the wave tile, 0 = nothing to do
+    int r;
+};
+
+template <bool INLINE>
+__device__ __forceinline__ TileRef locate(const PackArgs &a, uint32_t block, int wave) {
+    const uint32_t *tile_off = INLINE ? a.inl.tile_off : a.dev.tile_off;
+    const int64_t *elem_off = INLINE ? a.inl.elem_off : a.dev.elem_off;
+    const int64_t *pack_off = INLINE ? a.inl.pack_off : a.dev.pack_off;
+    const uint8_t *rbytes = INLINE ? a.inl.rbytes : a.dev.rbytes;
+    int lo = 0, hi = a.n_layers;            // largest lo with tile_off[lo] <= block
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tile_off[mid] <= block) lo = mid; else hi = mid;
+    }
+    const int64_t e_begin = elem_off[lo];
+    const int64_t n = elem_off[lo + 1] - e_begin;
+    const int64_t first = (int64_t)(block - tile_off[lo]) * kBlockTile +
+                          (int64_t)wave * kWaveTile;
+    TileRef t;
+    t.r = rbytes[lo];
+    t.elem = e_begin + first;
+    t.byte = pack_off[lo] + first * t.r;
+    const int64_t left = n - first;
+    t.len = left <= 0 ? 0 : (left < kWaveTile ? (int)left : kWaveTile);
+    return t;
 }
 
 }  // namespace adt

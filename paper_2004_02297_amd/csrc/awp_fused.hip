@@ -162,6 +162,30 @@ __global__ __launch_bounds__(kBlock) void redo_kernel(const FusedArgs a) {
     }
 }
 
+// Pack and truncate in one kernel from host-built tables (adt_pack_unpack): the
+// weights are read once and both the stream and the words Bitunpack would
+// return are written.
+template <bool INLINE>
+__global__ __launch_bounds__(kBlock) void pack_unpack_kernel(const PackUnpackArgs a) {
+    __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    const TileRef t = locate<INLINE>(a.p, blockIdx.x, wave);
+    if (t.len == 0) return;
+    const uint32_t *src = a.p.weights + t.elem;
+    uint8_t *stream = a.p.packed + t.byte;
+    uint32_t *wout = a.weights_out + t.elem;
+    uint32_t *lds = smem[wave];
+    double sum = 0.0;
+    uint32_t mag = 0u;
+    switch (t.r) {
+        case 1: fused_wave_tile<1, false, true>(src, stream, wout, t.len, lds, lane, sum, mag); break;
+        case 2: fused_wave_tile<2, false, true>(src, stream, wout, t.len, lds, lane, sum, mag); break;
+        case 3: fused_wave_tile<3, false, true>(src, stream, wout, t.len, lds, lane, sum, mag); break;
+        default: fused_wave_tile<4, false, true>(src, stream, wout, t.len, lds, lane, sum, mag); break;
+    }
+}
+
 // Algorithm 1 for all layers, then the stream offsets of the new byte counts.
 constexpr int kRuleBlock = 1024;
 constexpr int kRuleWaves = kRuleBlock / kWave;
@@ -176,34 +200,44 @@ __global__ __launch_bounds__(kRuleBlock) void rule_kernel(const RuleArgs a) {
         carry = 0;
     }
     __syncthreads();
-    for (int base = 0; base < a.n_layers; base += kRuleBlock) {
-        const int l = base + tid;
-        long long size = 0;
-        if (l < a.n_layers) {
-            const double now = a.stats[3 * l + 1];
-            int bits = a.bits[l];
-            if (!a.is_first) {
-                const double prev = a.l2_prev[l];
-                const double delta =
-                    prev == 0.0 ? (now == 0.0 ? 0.0 : __builtin_huge_val()) : (now - prev) / prev;
-                int counter = a.counter[l];
-                if (delta < a.T) ++counter;
-                if (counter == a.interval) {
-                    bits += a.n_bits;
-                    if (bits > 32) bits = 32;
-                    counter = 0;
-                }
-                a.counter[l] = counter;
-                a.bits[l] = bits;
+    // Phase 1: one thread per group.  The group's norm is the l2-norm over all
+    // weights of its layers (sum of the layers' sums of squares, index order).
+    for (int g = tid; g < a.n_groups; g += kRuleBlock) {
+        const int l0 = a.group_off[g], l1 = a.group_off[g + 1];
+        double sumsq = 0.0;
+        for (int l = l0; l < l1; ++l) sumsq += a.stats[3 * l];
+        const double now = sqrt(sumsq);
+        int bits = a.bits[g];
+        if (!a.is_first) {
+            const double prev = a.l2_prev[g];
+            const double delta =
+                prev == 0.0 ? (now == 0.0 ? 0.0 : __builtin_huge_val()) : (now - prev) / prev;
+            int counter = a.counter[g];
+            if (delta < a.T) ++counter;
+            if (counter == a.interval) {
+                bits += a.n_bits;
+                if (bits > 32) bits = 32;
+                counter = 0;
             }
-            a.l2_prev[l] = now;
-            const int r = (bits + 7) >> 3;
+            a.counter[g] = counter;
+            a.bits[g] = bits;
+        }
+        a.l2_prev[g] = now;
+        const int r = (bits + 7) >> 3;
+        for (int l = l0; l < l1; ++l) {
             if (r != (int)a.rbytes[l]) {
                 a.rbytes[l] = (uint8_t)r;
                 any_changed = 1;      // benign race: every writer stores 1
             }
-            size = (long long)(a.elem_off[l + 1] - a.elem_off[l]) * r;
         }
+    }
+    __syncthreads();
+    // Phase 2: stream offsets = exclusive prefix sum of n_l * r_l over the layers.
+    for (int base = 0; base < a.n_layers; base += kRuleBlock) {
+        const int l = base + tid;
+        long long size = 0;
+        if (l < a.n_layers)
+            size = (long long)(a.elem_off[l + 1] - a.elem_off[l]) * (int)a.rbytes[l];
         // exclusive prefix sum of `size` over the block, on top of `carry`
         long long incl = size;
 #pragma unroll
@@ -236,6 +270,13 @@ hipError_t launch_redo(const FusedArgs &a, bool write_w, hipStream_t stream) {
     const uint32_t grid = a.n_tiles < 2048u ? a.n_tiles : 2048u;
     return write_w ? launch(redo_kernel<true>, kKernelRedo, grid, kBlock, stream, a)
                    : launch(redo_kernel<false>, kKernelRedo, grid, kBlock, stream, a);
+}
+
+hipError_t launch_pack_unpack(const PackUnpackArgs &a, uint32_t n_tiles, bool inline_table,
+                              hipStream_t stream) {
+    return inline_table
+               ? launch(pack_unpack_kernel<true>, kKernelPackUnpack, n_tiles, kBlock, stream, a)
+               : launch(pack_unpack_kernel<false>, kKernelPackUnpack, n_tiles, kBlock, stream, a);
 }
 
 hipError_t launch_rule(const RuleArgs &a, hipStream_t stream) {

@@ -68,6 +68,30 @@ def check_pack_unpack(adt, w, off, rb, w_shift=0, p_shift=0):
         assert np.array_equal(gotw[lo:hi][seg], u[seg] & np.uint32(MASK[int(rb[l])]))
 
 
+def check_pack_unpack_fused(adt, w, off, rb, w_shift=0, p_shift=0):
+    """adt_pack_unpack with guard bytes and misaligned bases against the oracle."""
+    n = int(off[-1])
+    exp_stream = oracle.pack(w, off, rb)
+    exp_back = oracle.unpack(exp_stream, off, rb)
+    size, guard = exp_stream.size, 64
+    wbuf = torch.zeros(n + w_shift + 8, dtype=torch.float32, device="cuda")
+    wview = wbuf[w_shift:w_shift + n]
+    wview.copy_(torch.from_numpy(w))
+    pbuf = torch.full((size + p_shift + 2 * guard,), 0xA5, dtype=torch.uint8, device="cuda")
+    obuf = torch.zeros(n + w_shift + 2 * guard, dtype=torch.float32, device="cuda")
+    obuf.view(torch.int32).fill_(0x5A5A5A5A)
+    adt.adt_pack_unpack(wview, off, rb, out=pbuf[guard + p_shift:guard + p_shift + size],
+                        weights_out=obuf[guard + w_shift:guard + w_shift + n])
+    got = pbuf.cpu().numpy()
+    lo, hi = guard + p_shift, guard + p_shift + size
+    assert np.all(got[:lo] == 0xA5) and np.all(got[hi:] == 0xA5)
+    assert np.array_equal(got[lo:hi], exp_stream)
+    gotw = obuf.view(torch.int32).cpu().numpy().view(np.uint32)
+    lo, hi = guard + w_shift, guard + w_shift + n
+    assert np.all(gotw[:lo] == 0x5A5A5A5A) and np.all(gotw[hi:] == 0x5A5A5A5A)
+    assert np.array_equal(gotw[lo:hi], exp_back.view(np.uint32))
+
+
 def check_stats(adt, w, off, rtol=STATS_RTOL):
     exp = oracle.stats(w, off)
     got = adt.awp_layer_stats(dev(w), off).cpu().numpy()
@@ -92,6 +116,7 @@ def test_tiny_config(adt):
 @pytest.mark.parametrize("name,variant", [
     ("alexnet", "default"), ("resnet50", "default"),
     ("vgg16", "all2"), ("vgg16", "all3"), ("vgg16", "mixed"),
+    ("paper_alexnet", "default"), ("paper_vgga", "default"), ("paper_resnet34", "default"),
 ])
 def test_full_size_configs(adt, name, variant):
     ws = workloads.make_weight_set(name)
@@ -105,7 +130,11 @@ def test_full_size_configs(adt, name, variant):
     back = adt.adt_unpack(packed, off, rb)
     exp_back = oracle.unpack(exp_stream, off, rb)
     assert np.array_equal(back.view(torch.int32).cpu().numpy(), exp_back.view(np.int32))
-    del packed, back
+    # pack and truncate in one kernel: same stream, same words
+    packed2, back2 = adt.adt_pack_unpack(dw, off, rb)
+    assert torch.equal(packed2, packed)
+    assert torch.equal(back2.view(torch.int32), back.view(torch.int32))
+    del packed, back, packed2, back2
     if variant in ("default", "all2"):
         check_stats(adt, w, off)
 
@@ -132,6 +161,7 @@ def test_alexnet_hundred_passes_stay_identical(adt):
 def test_alignment_sweep(adt, w_shift, p_shift):
     off, rb, w = workloads.alignment_sweep_case()
     check_pack_unpack(adt, w, off, rb, w_shift, p_shift)
+    check_pack_unpack_fused(adt, w, off, rb, w_shift, p_shift)
 
 
 @pytest.mark.parametrize("r", [1, 2, 3, 4])
@@ -171,6 +201,7 @@ def test_many_layers_use_the_device_table(adt):
     off, rb, w = workloads.ragged_case(sizes, rb, seed=78)
     for _ in range(6):     # more calls than ring slots
         check_pack_unpack(adt, w, off, rb, 1, 3)
+    check_pack_unpack_fused(adt, w, off, rb, 1, 3)
     off2, _, w2 = workloads.ragged_case(sizes, rb, seed=79, he=True)
     for _ in range(6):
         check_stats(adt, w2, off2)

@@ -24,7 +24,7 @@ def adt():
 
 
 def run_trajectory(adt, sizes, steps, T, interval, n_bits, init_bits, seed, w_shift=0,
-                   p_shift=0, truncated=True):
+                   p_shift=0, truncated=True, groups=None):
     rng = np.random.default_rng(seed)
     off = workloads.offsets_from_sizes(sizes)
     L, N = len(sizes), int(off[-1])
@@ -36,9 +36,11 @@ def run_trajectory(adt, sizes, steps, T, interval, n_bits, init_bits, seed, w_sh
     obuf = torch.zeros(N + w_shift + 4, dtype=torch.float32, device="cuda")
     out = obuf[w_shift:w_shift + N] if truncated else None
 
-    ib = None if init_bits is None else np.full(L, init_bits, np.int32)
-    plan = adt.AwpPlan(off, T, interval, n_bits, init_bits=ib)
-    ost = oracle.AwpState(L, 8 if init_bits is None else init_bits)
+    grp = np.arange(L + 1, dtype=np.int32) if groups is None else np.asarray(groups, np.int32)
+    G = grp.size - 1
+    ib = None if init_bits is None else np.full(G, init_bits, np.int32)
+    plan = adt.AwpPlan(off, T, interval, n_bits, init_bits=ib, group_offsets=groups)
+    ost = oracle.AwpState(G, 8 if init_bits is None else init_bits)
     n_changes = 0
     prev = None
     for step in range(steps):
@@ -54,7 +56,16 @@ def run_trajectory(adt, sizes, steps, T, interval, n_bits, init_bits, seed, w_sh
         o_stats = oracle.stats(hw, off)
         np.testing.assert_allclose(got["stats"], o_stats, rtol=1e-10, atol=0.0)
         np.testing.assert_array_equal(got["stats"][:, 2], o_stats[:, 2])
-        orb = oracle.awp_update(ost, o_stats[:, 1], T, interval, n_bits)
+        if groups is None:
+            orb = oracle.awp_update(ost, o_stats[:, 1], T, interval, n_bits)
+        else:
+            gb = oracle.awp_update(ost, oracle.group_norms(hw, off, grp), T, interval, n_bits)
+            orb = np.repeat(gb, np.diff(grp)).astype(np.uint8)
+            # the three-call route through the host helpers agrees as well
+            hb = adt.awp_expand_group_bytes(gb, grp)
+            assert np.array_equal(hb, orb)
+            np.testing.assert_allclose(adt.awp_group_norms(got["stats"], grp),
+                                       oracle.group_norms(hw, off, grp), rtol=1e-10)
         assert np.array_equal(got["bytes"], orb), f"step {step}"
         assert np.array_equal(got["bits"], ost.bits) and np.array_equal(got["counter"], ost.counter)
         exp_stream = oracle.pack(hw, off, orb)
@@ -100,6 +111,37 @@ def test_plan_many_layers(adt):
     sizes = rng.integers(0, 3000, size=2500).tolist()     # rule kernel loops over 1024-layer chunks
     n = run_trajectory(adt, sizes, steps=6, T=0.0, interval=1, n_bits=8, init_bits=None, seed=4)
     assert n >= 1
+
+
+def test_plan_with_layer_groups(adt):
+    # groups of uneven length, an empty group and single-layer groups
+    sizes = [300, 4096, 5000, 1, 7000, 64, 8192, 33, 2, 9000, 12]
+    groups = [0, 1, 3, 3, 6, 7, 10, 11]
+    n = run_trajectory(adt, sizes, steps=20, T=0.0, interval=2, n_bits=8, init_bits=None,
+                       seed=5, groups=groups)
+    assert n >= 4
+
+
+def test_plan_resnet34_block_groups_full_size(adt):
+    ws = workloads.make_weight_set("paper_resnet34")
+    off, N, L = ws.layer_offsets, ws.n_weights, ws.n_layers
+    grp = workloads.paper_resnet34_group_offsets()
+    w = torch.from_numpy(ws.weights).cuda()
+    packed = torch.empty(4 * N, dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(w)
+    start = (np.arange(grp.size - 1) % 4 + 1).astype(np.int32) * 8     # 1,2,3,4 bytes per block
+    plan = adt.AwpPlan(off, -2e-5, 2000, 8, init_bits=start, group_offsets=grp)
+    plan.step(w, packed, out)
+    plan.step(w, packed, out)
+    got = plan.read()
+    rb = np.repeat((start // 8).astype(np.uint8), np.diff(grp))
+    assert np.array_equal(got["bytes"], rb) and np.array_equal(got["bits"], start)
+    exp = oracle.pack(ws.weights, off, rb)
+    assert got["packed_size"] == exp.size
+    assert np.array_equal(packed[:exp.size].cpu().numpy(), exp)
+    assert np.array_equal(out.view(torch.int32).cpu().numpy(),
+                          oracle.unpack(exp, off, rb).view(np.int32))
+    plan.close()
 
 
 def test_plan_full_size_vgg16(adt):

@@ -48,8 +48,12 @@ def test_packed_size(adt):
 
 def test_config_sizes():
     n = {k: int(workloads.layer_sizes(f()).sum()) for k, f in workloads.SHAPES.items()}
-    assert n == {"tiny": 10160, "alexnet": 61090496, "resnet50": 25502912, "vgg16": 138344128}
+    assert n == {"tiny": 10160, "alexnet": 61090496, "resnet50": 25502912, "vgg16": 138344128,
+                 "paper_alexnet": 75328192, "paper_vgga": 129574592, "paper_resnet34": 21198016}
     assert len(workloads.resnet50_shapes()) == 54
+    # the paper's Table 1: 5 conv + 4 FC, 8 conv + 3 FC, 33 conv + 1 FC
+    assert [len(workloads.SHAPES[k]()) for k in ("paper_alexnet", "paper_vgga", "paper_resnet34")] \
+        == [9, 11, 34]
 
 
 def test_invalid_arguments_fail_before_any_launch(adt):
@@ -120,3 +124,23 @@ def test_awp_update_matches_oracle_on_random_norm_sequences(adt):
 def test_awp_update_paper_example_bytes(adt):
     st = adt.AwpState(4, init_bits=14)
     assert adt.awp_update(st, np.ones(4), -2e-3, 4000).tolist() == [2, 2, 2, 2]
+
+
+def test_group_helpers_match_oracle(adt):
+    shapes = workloads.paper_resnet34_shapes()
+    off = workloads.offsets_from_sizes(workloads.layer_sizes(shapes))
+    grp = workloads.paper_resnet34_group_offsets()
+    assert len(grp) == 19 and grp[-1] == len(shapes) == 34
+    small = [s for s in shapes[:7]]
+    off = workloads.offsets_from_sizes(workloads.layer_sizes(small))
+    w = workloads.he_normal_weights(small, seed=6)
+    g = np.array([0, 1, 3, 5, 7], dtype=np.int32)
+    st = oracle.stats(w, off)
+    got = adt.awp_group_norms(st, g)
+    np.testing.assert_allclose(got, oracle.group_norms(w, off, g), rtol=1e-13)
+    rb = adt.awp_expand_group_bytes(np.array([1, 2, 3, 4], np.uint8), g)
+    assert rb.tolist() == [1, 2, 2, 3, 3, 4, 4]
+    with pytest.raises(adt.AdtError):
+        adt.awp_group_norms(st, np.array([0, 3, 2, 7], np.int32))
+    with pytest.raises(adt.AdtError):
+        adt.awp_group_norms(st, np.array([1, 7], np.int32))

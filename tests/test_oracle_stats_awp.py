@@ -146,3 +146,28 @@ def test_zero_previous_norm():
     hist = run([[0.0], [0.0], [1.0], [1.0]], T=0.5, interval=1)
     # 0 -> 0: delta = 0 < T counts; 0 -> 1: delta = +inf does not; 1 -> 1 counts
     assert [int(h[0][0]) for h in hist] == [8, 16, 16, 24]
+
+
+# ---------------------------------------------------------------- layer groups
+def test_group_norms():
+    shapes = workloads.paper_resnet34_shapes()[:9]
+    w = workloads.he_normal_weights(shapes, seed=4)
+    off = workloads.offsets_from_sizes(workloads.layer_sizes(shapes))
+    L = len(shapes)
+    # one group over everything is the norm of the whole vector (library routine)
+    g_all = oracle.group_norms(w, off, [0, L])
+    assert g_all[0] == pytest.approx(np.linalg.norm(w.astype(np.float64)), rel=1e-14)
+    # one group per layer reproduces the per-layer norms exactly
+    per_layer = oracle.group_norms(w, off, np.arange(L + 1))
+    assert per_layer.tolist() == oracle.stats(w, off)[:, 1].tolist()
+    # blocks of two layers: Pythagoras over the members, an empty group gives 0
+    grp = [0, 1, 3, 3, 5, 7, 9]
+    got = oracle.group_norms(w, off, grp)
+    st = oracle.stats(w, off)
+    for g in range(len(grp) - 1):
+        members = st[grp[g]:grp[g + 1], 0]
+        assert got[g] == pytest.approx(math.sqrt(float(members.sum())), rel=1e-14, abs=0.0)
+    assert got[2] == 0.0
+    # 3-4-5 across two layers
+    w2 = np.array([3.0, 0.0, 4.0], dtype=np.float32)
+    assert oracle.group_norms(w2, np.array([0, 1, 3]), [0, 2])[0] == 5.0

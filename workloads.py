@@ -67,15 +67,61 @@ def vgg16_shapes() -> List[Shape]:
     return shapes
 
 
+# The three networks of the paper's own evaluation (its Table 1, 200-class
+# heads).  The table gives filter sizes and channel counts only; the first
+# fully-connected layer is taken to see the usual 6x6x256 (AlexNet) and 7x7x512
+# (VGG) feature maps.
+def paper_alexnet_shapes() -> List[Shape]:
+    """Modified AlexNet: 5 conv + 4 FC (an extra FC-4096), FC-200 head."""
+    return [
+        _conv(64, 3, 11), _conv(192, 64, 5), _conv(384, 192, 3), _conv(384, 384, 3),
+        _conv(256, 384, 3),
+        _fc(4096, 9216), _fc(4096, 4096), _fc(4096, 4096), _fc(200, 4096),
+    ]
+
+
+def paper_vgga_shapes() -> List[Shape]:
+    """VGG configuration A: 8 conv + 3 FC, FC-200 head (129,574,592 weights)."""
+    cfg = [(64, 3), (128, 64), (256, 128), (256, 256), (512, 256), (512, 512),
+           (512, 512), (512, 512)]
+    return [_conv(o, i, 3) for o, i in cfg] + [_fc(4096, 25088), _fc(4096, 4096),
+                                              _fc(200, 4096)]
+
+
+def paper_resnet34_shapes() -> List[Shape]:
+    """ResNet-34 as the paper counts it: 33 conv (stem + 16 two-conv building
+    blocks) + FC-200."""
+    shapes: List[Shape] = [_conv(64, 3, 7)]
+    in_ch = 64
+    for width, blocks in ((64, 3), (128, 4), (256, 6), (512, 3)):
+        for _ in range(blocks):
+            shapes.append(_conv(width, in_ch, 3))
+            shapes.append(_conv(width, width, 3))
+            in_ch = width
+    shapes.append(_fc(200, 512))
+    return shapes
+
+
+def paper_resnet34_group_offsets() -> np.ndarray:
+    """Layer-index ranges of the precision groups for ResNet (Section IV-B: the
+    paper adapts precision per building block): stem, 16 blocks of two
+    convolutions, head.  Group g covers layers [out[g], out[g+1])."""
+    return np.array([0, 1] + [1 + 2 * (b + 1) for b in range(16)] + [34], dtype=np.int32)
+
+
 SHAPES = {
     "tiny": tiny_shapes,
     "alexnet": alexnet_shapes,
     "resnet50": resnet50_shapes,
     "vgg16": vgg16_shapes,
+    "paper_alexnet": paper_alexnet_shapes,
+    "paper_vgga": paper_vgga_shapes,
+    "paper_resnet34": paper_resnet34_shapes,
 }
 
 # Seed per configuration (Tiny is seed 0); byte-count draws use seed + 1000.
-SEEDS = {"tiny": 0, "alexnet": 1, "resnet50": 2, "vgg16": 3}
+SEEDS = {"tiny": 0, "alexnet": 1, "resnet50": 2, "vgg16": 3,
+         "paper_alexnet": 11, "paper_vgga": 12, "paper_resnet34": 13}
 
 
 def layer_sizes(shapes: Sequence[Shape]) -> np.ndarray:
@@ -148,7 +194,7 @@ def config_bytes(name: str, variant: str = "default") -> np.ndarray:
     seed = SEEDS[name]
     if name == "tiny":
         return np.array([2, 3, 4], dtype=np.uint8)
-    if name == "alexnet":
+    if name in ("alexnet", "paper_alexnet", "paper_vgga", "paper_resnet34"):
         return draw_bytes(L, (1, 2, 3, 4), seed)
     if name == "resnet50":
         return draw_bytes(L, (2, 3, 4), seed)
