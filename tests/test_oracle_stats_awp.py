@@ -156,7 +156,7 @@ def test_group_norms():
     L = len(shapes)
     # one group over everything is the norm of the whole vector (library routine)
     g_all = oracle.group_norms(w, off, [0, L])
-    assert g_all[0] == pytest.approx(np.linalg.norm(w.astype(np.float64)), rel=1e-14)
+    assert g_all[0] == pytest.approx(np.linalg.norm(w.astype(np.float64)), rel=1e-12)
     # one group per layer reproduces the per-layer norms exactly
     per_layer = oracle.group_norms(w, off, np.arange(L + 1))
     assert per_layer.tolist() == oracle.stats(w, off)[:, 1].tolist()
@@ -166,7 +166,7 @@ def test_group_norms():
     st = oracle.stats(w, off)
     for g in range(len(grp) - 1):
         members = st[grp[g]:grp[g + 1], 0]
-        assert got[g] == pytest.approx(math.sqrt(float(members.sum())), rel=1e-14, abs=0.0)
+        assert got[g] == pytest.approx(math.sqrt(float(members.sum())), rel=1e-12, abs=0.0)
     assert got[2] == 0.0
     # 3-4-5 across two layers
     w2 = np.array([3.0, 0.0, 4.0], dtype=np.float32)
