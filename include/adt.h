@@ -92,6 +92,24 @@ int adt_unpack(const uint8_t *packed, const int64_t *layer_offsets,
                float *weights_out, adt_stream_t stream);
 
 /*
+ * Bitunpack straight to a 16-bit compute format (the paper's related-work
+ * section proposes decompressing to half precision to combine the method with
+ * mixed-precision training).  Same stream and tables as adt_unpack; element i
+ * of `out` is made from the FP32 word w'_i that adt_unpack would return:
+ *   ADT_OUT_BF16  the top 16 bits of w'_i (truncation, as ADT itself truncates;
+ *                 exact for r <= 2)
+ *   ADT_OUT_FP16  w'_i converted to IEEE binary16, round to nearest even,
+ *                 overflow to infinity, NaN stays NaN (payload not preserved)
+ *   out  device, N 16-bit elements, 2-byte aligned (4-byte alignment of every
+ *        layer start is the fast case); must not overlap `packed`
+ */
+#define ADT_OUT_BF16 1
+#define ADT_OUT_FP16 2
+int adt_unpack16(const uint8_t *packed, const int64_t *layer_offsets,
+                 const uint8_t *bytes_per_layer, int n_layers, uint16_t *out, int format,
+                 adt_stream_t stream);
+
+/*
  * adt_pack and adt_unpack of the same weights in one kernel: the weights are
  * read once; `out` receives the packed stream exactly as adt_pack writes it
  * and `weights_out` the FP32 words adt_unpack would return from that stream
@@ -212,7 +230,7 @@ const char *adt_last_error(void);
  * ADT_NKERNELS entries, indexed as adt_kernel_name names them) and forgets
  * them.
  */
-#define ADT_NKERNELS 8
+#define ADT_NKERNELS 9
 typedef struct adt_kernel_time {
     int64_t launches;
     double total_ms;

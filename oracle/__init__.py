@@ -105,6 +105,19 @@ def unpack(packed: np.ndarray, layer_offsets, bytes_per_layer) -> np.ndarray:
     return out
 
 
+def unpack16(packed: np.ndarray, layer_offsets, bytes_per_layer, fmt: str) -> np.ndarray:
+    """Bitunpack followed by a conversion to a 16-bit format, as uint16 bit
+    patterns: "bf16" keeps the top 16 bits of each unpacked word, "fp16" is the
+    IEEE binary16 value nearest to it (ties to even; numpy's conversion)."""
+    w = unpack(packed, layer_offsets, bytes_per_layer)
+    if fmt == "bf16":
+        return (w.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+    if fmt == "fp16":
+        with np.errstate(over="ignore"):
+            return w.astype(np.float16).view(np.uint16)
+    raise ValueError("fmt must be 'bf16' or 'fp16'")
+
+
 def stats(weights: np.ndarray, layer_offsets) -> np.ndarray:
     """float64[L, 3]: sum of squares, l2-norm, largest magnitude per layer."""
     off, _, L = _tables(layer_offsets)

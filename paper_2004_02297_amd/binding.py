@@ -49,6 +49,8 @@ def load_library():
     lib.adt_pack.argtypes = [P, P, P, I, P, P]
     lib.adt_unpack.restype = I
     lib.adt_unpack.argtypes = [P, P, P, I, P, P]
+    lib.adt_unpack16.restype = I
+    lib.adt_unpack16.argtypes = [P, P, P, I, P, I, P]
     lib.adt_pack_unpack.restype = I
     lib.adt_pack_unpack.argtypes = [P, P, P, I, P, P, P]
     lib.awp_layer_stats.restype = I
@@ -172,6 +174,28 @@ def adt_unpack(packed, layer_offsets, bytes_per_layer, out=None, stream=None):
             raise ValueError("out size does not match layer_offsets[-1]")
     _check(load_library().adt_unpack(p.data_ptr() or None, _hptr(off), _hptr(rb), L,
                                      out.data_ptr() or None, _stream(stream)))
+    return out
+
+
+def adt_unpack16(packed, layer_offsets, bytes_per_layer, fmt: str, out=None, stream=None):
+    """adt_unpack16: device uint8 stream -> device bfloat16 / float16 [N]."""
+    import torch
+    dtype, code = {"bf16": (torch.bfloat16, 1), "fp16": (torch.float16, 2)}[fmt]
+    off = _host(layer_offsets, np.int64)
+    rb = _host(bytes_per_layer, np.uint8)
+    L = off.size - 1
+    if rb.size != L:
+        raise ValueError("bytes_per_layer must have n_layers entries")
+    p = _dev_tensor(packed, torch.uint8, "packed")
+    if p.numel() < adt_packed_size(off, rb):
+        raise ValueError("packed is smaller than the packed size")
+    n = int(off[-1])
+    if out is None:
+        out = torch.empty(n, dtype=dtype, device=p.device)
+    elif _dev_tensor(out, dtype, "out").numel() != n:
+        raise ValueError("out size does not match layer_offsets[-1]")
+    _check(load_library().adt_unpack16(p.data_ptr() or None, _hptr(off), _hptr(rb), L,
+                                       out.data_ptr() or None, code, _stream(stream)))
     return out
 
 

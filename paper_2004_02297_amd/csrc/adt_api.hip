@@ -16,11 +16,12 @@
 #include "../../include/adt.h"
 #include "adt_launch.h"
 #include "adt_tables.h"
+#include "adt_tile_ops.h"
 
 namespace adt {
 hipError_t launch_pack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
                        hipStream_t stream);
-hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
+hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table, int out_format,
                          hipStream_t stream);
 hipError_t launch_stats(const StatsArgs &a, const StatsFinalArgs &f, uint32_t n_tiles,
                         bool inline_table, hipStream_t stream);
@@ -54,6 +55,8 @@ struct awp_plan {
 };
 
 static_assert(ADT_NKERNELS == adt::kNumKernels, "adt.h and adt_launch.h disagree");
+static_assert(ADT_OUT_BF16 == adt::kOutBf16 && ADT_OUT_FP16 == adt::kOutFp16,
+              "adt.h and adt_tile_ops.h disagree");
 
 namespace {
 
@@ -195,7 +198,7 @@ int check_groups(const int32_t *group_offsets, int n_groups, int n_layers,
     return ADT_OK;
 }
 
-enum Direction { kPack, kUnpack, kPackUnpack };
+enum Direction { kPack, kUnpack, kPackUnpack, kUnpackBf16, kUnpackFp16 };
 
 int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
                    const uint8_t *rb, int n_layers, const void *packed, adt_stream_t stream,
@@ -205,7 +208,10 @@ int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
     const int64_t n = n_layers ? off[n_layers] : 0;
     if (n_layers == 0 || n == 0) return ADT_OK;
     if (!weights || !packed) return fail(ADT_EINVAL, "null device pointer");
-    if ((uintptr_t)weights & 3u) return fail(ADT_EALIGN, "FP32 buffer is not 4-byte aligned");
+    const bool out16 = dir == kUnpackBf16 || dir == kUnpackFp16;
+    if ((uintptr_t)weights & (out16 ? 1u : 3u))
+        return fail(ADT_EALIGN, out16 ? "16-bit buffer is not 2-byte aligned"
+                                      : "FP32 buffer is not 4-byte aligned");
     if (dir == kPackUnpack) {
         if (!weights_out) return fail(ADT_EINVAL, "weights_out is null");
         if ((uintptr_t)weights_out & 3u)
@@ -272,8 +278,10 @@ int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
         if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(table)");
     }
     hipError_t e = dir == kPack     ? adt::launch_pack(a, n_tiles, inl, hs)
-                   : dir == kUnpack ? adt::launch_unpack(a, n_tiles, inl, hs)
-                                    : adt::launch_pack_unpack(pu, n_tiles, inl, hs);
+                   : dir == kUnpack ? adt::launch_unpack(a, n_tiles, inl, 0, hs)
+                   : dir == kUnpackBf16 ? adt::launch_unpack(a, n_tiles, inl, ADT_OUT_BF16, hs)
+                   : dir == kUnpackFp16 ? adt::launch_unpack(a, n_tiles, inl, ADT_OUT_FP16, hs)
+                                        : adt::launch_pack_unpack(pu, n_tiles, inl, hs);
     if (!inl) {
         // guard the slot even if the launch failed: the copy may be in flight
         if (hipEventRecord(slot->ev, hs) == hipSuccess) slot->pending = true;
@@ -326,6 +334,15 @@ int adt_unpack(const uint8_t *packed, const int64_t *layer_offsets,
                adt_stream_t stream) {
     return pack_or_unpack(kUnpack, weights_out, layer_offsets, bytes_per_layer, n_layers,
                           packed, stream);
+}
+
+int adt_unpack16(const uint8_t *packed, const int64_t *layer_offsets,
+                 const uint8_t *bytes_per_layer, int n_layers, uint16_t *out, int format,
+                 adt_stream_t stream) {
+    if (format != ADT_OUT_BF16 && format != ADT_OUT_FP16)
+        return fail(ADT_EINVAL, "format must be ADT_OUT_BF16 or ADT_OUT_FP16");
+    return pack_or_unpack(format == ADT_OUT_BF16 ? kUnpackBf16 : kUnpackFp16, out, layer_offsets,
+                          bytes_per_layer, n_layers, packed, stream);
 }
 
 int adt_pack_unpack(const float *weights, const int64_t *layer_offsets,
@@ -786,6 +803,7 @@ const char *adt_kernel_name(int kernel) {
         case adt::kKernelRule: return "rule_kernel";
         case adt::kKernelRedo: return "redo_kernel";
         case adt::kKernelPackUnpack: return "pack_unpack_kernel";
+        case adt::kKernelUnpack16: return "unpack16_kernel";
         default: return "";
     }
 }

@@ -21,7 +21,8 @@ enum KernelId {
     kKernelRule = 5,
     kKernelRedo = 6,
     kKernelPackUnpack = 7,
-    kNumKernels = 8
+    kKernelUnpack16 = 8,
+    kNumKernels = 9
 };
 
 // Defined in adt_api.hip.  True (and a fresh event pair, owned by the timing

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kBlock) void pack_kernel(const PackArgs a) {
     }
 }
 
-template <bool INLINE>
+template <bool INLINE, int OUT>
 __global__ __launch_bounds__(kBlock) void unpack_kernel(const PackArgs a) {
     __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -57,15 +57,18 @@ __global__ __launch_bounds__(kBlock) void unpack_kernel(const PackArgs a) {
     const TileRef t = locate<INLINE>(a, blockIdx.x, wave);
     if (t.len == 0) return;
     const uint8_t *src = a.packed + t.byte;
-    uint32_t *dst = const_cast<uint32_t *>(a.weights) + t.elem;
+    // a.weights is the output buffer here: FP32 words or 16-bit elements
+    void *dst = OUT == kOutFp32
+                    ? (void *)(const_cast<uint32_t *>(a.weights) + t.elem)
+                    : (void *)((uint16_t *)const_cast<uint32_t *>(a.weights) + t.elem);
     const uint8_t *lo = a.packed;
     const uint8_t *hi = a.packed + a.packed_size;
     uint32_t *lds = smem[wave];
     switch (t.r) {
-        case 1: unpack_wave_tile<1>(src, dst, t.len, lo, hi, lds, lane); break;
-        case 2: unpack_wave_tile<2>(src, dst, t.len, lo, hi, lds, lane); break;
-        case 3: unpack_wave_tile<3>(src, dst, t.len, lo, hi, lds, lane); break;
-        default: unpack_wave_tile<4>(src, dst, t.len, lo, hi, lds, lane); break;
+        case 1: unpack_wave_tile<1, OUT>(src, dst, t.len, lo, hi, lds, lane); break;
+        case 2: unpack_wave_tile<2, OUT>(src, dst, t.len, lo, hi, lds, lane); break;
+        case 3: unpack_wave_tile<3, OUT>(src, dst, t.len, lo, hi, lds, lane); break;
+        default: unpack_wave_tile<4, OUT>(src, dst, t.len, lo, hi, lds, lane); break;
     }
 }
 
@@ -75,10 +78,19 @@ hipError_t launch_pack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
                         : launch(pack_kernel<false>, kKernelPack, n_tiles, kBlock, stream, a);
 }
 
-hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
+hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table, int out_format,
                          hipStream_t stream) {
-    return inline_table ? launch(unpack_kernel<true>, kKernelUnpack, n_tiles, kBlock, stream, a)
-                        : launch(unpack_kernel<false>, kKernelUnpack, n_tiles, kBlock, stream, a);
+    void (*k)(PackArgs);
+    if (inline_table)
+        k = out_format == kOutFp32   ? unpack_kernel<true, kOutFp32>
+            : out_format == kOutBf16 ? unpack_kernel<true, kOutBf16>
+                                     : unpack_kernel<true, kOutFp16>;
+    else
+        k = out_format == kOutFp32   ? unpack_kernel<false, kOutFp32>
+            : out_format == kOutBf16 ? unpack_kernel<false, kOutBf16>
+                                     : unpack_kernel<false, kOutFp16>;
+    return launch(k, out_format == kOutFp32 ? kKernelUnpack : kKernelUnpack16, n_tiles, kBlock,
+                  stream, a);
 }
 
 }  // namespace adt

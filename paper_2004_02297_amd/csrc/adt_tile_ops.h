@@ -4,6 +4,7 @@
 // wave-tile movers that stage the byte stream through a wave-private LDS slice.
 #pragma once
 
+#include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -218,18 +219,69 @@ __device__ __forceinline__ void pack_wave_tile(const uint32_t *__restrict__ src,
 }
 
 // ---------------------------------------------------------------------------
+// Output formats of unpack: the FP32 word of Algorithm 5, or a 16-bit compute
+// format made from it (the combination with mixed-precision training that the
+// paper's related-work section proposes).
+// ---------------------------------------------------------------------------
+constexpr int kOutFp32 = 0;
+constexpr int kOutBf16 = 1;   // top 16 bits of the word (truncation, like ADT itself)
+constexpr int kOutFp16 = 2;   // binary16, round to nearest even, overflow to infinity
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef u32x2 u32x2_a4 __attribute__((aligned(4)));
+
+template <int OUT>
+__device__ __forceinline__ uint32_t to_half_bits(uint32_t word) {
+    if (OUT == kOutBf16) return word >> 16;
+    return (uint32_t)__half_as_ushort(__float2half_rn(__uint_as_float(word)));
+}
+
+// Store the four unpacked words of chunk starting at tile element e0.
+// dst: tile start; FP32 (4-byte aligned) or 16-bit elements (2-byte aligned).
+template <int OUT>
+__device__ __forceinline__ void store_unpacked(void *dst, int e0, int len, const u32x4 u,
+                                               bool dst_dword_aligned) {
+    if (OUT == kOutFp32) {
+        uint32_t *d = (uint32_t *)dst;
+        if (e0 + 4 <= len) {
+            store_fp32x4(d + e0, u);
+        } else {
+            d[e0] = u.x;
+            if (e0 + 1 < len) d[e0 + 1] = u.y;
+            if (e0 + 2 < len) d[e0 + 2] = u.z;
+        }
+    } else {
+        uint16_t *d = (uint16_t *)dst;
+        const uint32_t h0 = to_half_bits<OUT>(u.x), h1 = to_half_bits<OUT>(u.y),
+                       h2 = to_half_bits<OUT>(u.z), h3 = to_half_bits<OUT>(u.w);
+        if (e0 + 4 <= len && dst_dword_aligned) {
+            u32x2 o;
+            o.x = h0 | (h1 << 16);
+            o.y = h2 | (h3 << 16);
+            __builtin_nontemporal_store(o, (u32x2_a4 *)(d + e0));
+        } else {
+            if (e0 < len) d[e0] = (uint16_t)h0;
+            if (e0 + 1 < len) d[e0 + 1] = (uint16_t)h1;
+            if (e0 + 2 < len) d[e0 + 2] = (uint16_t)h2;
+            if (e0 + 3 < len) d[e0 + 3] = (uint16_t)h3;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Unpack one wave tile: len*R stream bytes at src -> `len` FP32 words at dst.
 // [buf_lo, buf_hi) is the whole packed buffer: a 16-byte piece inside it may
 // be read whole even where it reaches into a neighbouring tile.
 // ---------------------------------------------------------------------------
-template <int R>
+template <int R, int OUT = kOutFp32>
 __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src,
-                                                 uint32_t *__restrict__ dst, int len,
+                                                 void *__restrict__ dst, int len,
                                                  const uint8_t *buf_lo,
                                                  const uint8_t *buf_hi, uint32_t *lds,
                                                  int lane) {
     const uint32_t s = (uint32_t)((uintptr_t)src & 15u);   // wave uniform
     const bool full = (len == kWaveTile);
+    const bool dst_dw = ((uintptr_t)dst & 3u) == 0;        // wave uniform
 
     if (full && s == 0) {
         constexpr int kPieces = R * kChunksPerLane / 4;     // 16-byte pieces per lane
@@ -246,7 +298,7 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
             uint32_t y[4];
 #pragma unroll
             for (int t = 0; t < R; ++t) y[t] = lds[c * R + t];
-            store_fp32x4(dst + 4 * c, shift_to_top<R>(y));
+            store_unpacked<OUT>(dst, 4 * c, len, shift_to_top<R>(y), dst_dw);
         }
         return;
     }
@@ -287,14 +339,7 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
             uint32_t y[4];
 #pragma unroll
             for (int t = 0; t < R; ++t) y[t] = funnel(x[t + 1], x[t], sh);
-            const u32x4 u = shift_to_top<R>(y);
-            if (e0 + 4 <= len) {
-                store_fp32x4(dst + e0, u);
-            } else {
-                dst[e0] = u.x;
-                if (e0 + 1 < len) dst[e0 + 1] = u.y;
-                if (e0 + 2 < len) dst[e0 + 2] = u.z;
-            }
+            store_unpacked<OUT>(dst, e0, len, shift_to_top<R>(y), dst_dw);
         }
     }
 }

@@ -308,3 +308,42 @@ def test_ablation_variants_give_the_same_bytes(adt, variant):
         adt.adt_ablation(v, True, back, off, rb, p)
         assert np.array_equal(back.view(torch.int32).cpu().numpy(),
                               oracle.unpack(exp, off, rb).view(np.int32))
+
+
+# ------------------------------------------------------------------ 16-bit unpack
+@pytest.mark.parametrize("fmt", ["bf16", "fp16"])
+@pytest.mark.parametrize("elem_shift,p_shift", [(0, 0), (1, 3)])
+def test_unpack16_ragged(adt, fmt, elem_shift, p_shift):
+    off, rb, w = workloads.alignment_sweep_case()
+    w = w.copy()
+    w[::7] = workloads.he_normal_weights([(1, 50, 1, 1)], seed=3)[0]     # some ordinary values too
+    stream = oracle.pack(w, off, rb)
+    exp = oracle.unpack16(stream, off, rb, fmt)
+    n, guard = int(off[-1]), 32
+    pbuf = torch.zeros(stream.size + p_shift + 16, dtype=torch.uint8, device="cuda")
+    pview = pbuf[p_shift:p_shift + stream.size]
+    pview.copy_(torch.from_numpy(stream))
+    dtype = torch.bfloat16 if fmt == "bf16" else torch.float16
+    obuf = torch.zeros(n + elem_shift + 2 * guard, dtype=dtype, device="cuda")
+    obuf.view(torch.int16).fill_(0x5A5A)
+    adt.adt_unpack16(pview, off, rb, fmt, out=obuf[guard + elem_shift:guard + elem_shift + n])
+    got = obuf.view(torch.int16).cpu().numpy().view(np.uint16)
+    lo, hi = guard + elem_shift, guard + elem_shift + n
+    assert np.all(got[:lo] == 0x5A5A) and np.all(got[hi:] == 0x5A5A)
+    got = got[lo:hi]
+    if fmt == "bf16":
+        assert np.array_equal(got, exp)
+    else:
+        nan = (exp & 0x7C00 == 0x7C00) & (exp & 0x03FF != 0)
+        assert np.array_equal(got[~nan], exp[~nan])
+        assert np.all((got[nan] & 0x7C00) == 0x7C00) and np.all((got[nan] & 0x03FF) != 0)
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "fp16"])
+def test_unpack16_full_size(adt, fmt):
+    ws = workloads.make_weight_set("alexnet")
+    rb = workloads.config_bytes("alexnet")
+    stream = oracle.pack(ws.weights, ws.layer_offsets, rb)
+    got = adt.adt_unpack16(dev(stream), ws.layer_offsets, rb, fmt)
+    assert np.array_equal(got.view(torch.int16).cpu().numpy().view(np.uint16),
+                          oracle.unpack16(stream, ws.layer_offsets, rb, fmt))
