@@ -174,7 +174,9 @@ int awp_update(const double *l2_now, double *l2_prev, int32_t *counter,
  *   weights_out    device, N floats, or NULL to skip the truncated copy; must
  *                  not overlap weights or packed
  * Calls on one plan must be issued from one thread at a time and on one stream
- * (or on streams ordered by the caller).  The step allocates nothing.
+ * (or on streams ordered by the caller).  The step allocates nothing and does
+ * not wait for the GPU, so it may be captured into a HIP graph and replayed:
+ * all state that changes from batch to batch lives on the device.
  * awp_plan_read waits for the steps enqueued so far and copies the state to
  * host arrays (any pointer may be NULL): stats n_layers*AWP_NSTATS doubles,
  * bits / counter / bytes n_layers entries, packed_size one value.

@@ -50,7 +50,7 @@ struct awp_plan {
     int64_t *elem_off = nullptr, *pack_off = nullptr, *packed_size = nullptr;
     uint32_t *tile_off = nullptr, *partial_absmax = nullptr;
     uint8_t *rbytes = nullptr;
-    int32_t *bits = nullptr, *counter = nullptr, *changed = nullptr;
+    int32_t *bits = nullptr, *counter = nullptr, *changed = nullptr, *steps_done = nullptr;
     double *l2_prev = nullptr, *stats = nullptr, *partial_sumsq = nullptr;
 };
 
@@ -519,7 +519,7 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     const size_t o_prev = take(8 * G), o_stats = take(24 * L), o_psum = take(8 * (size_t)pl->n_tiles);
     const size_t o_tile = take(4 * L1), o_pmax = take(4 * (size_t)pl->n_tiles);
     const size_t o_bits = take(4 * G), o_cnt = take(4 * G), o_grp = take(4 * (G + 1));
-    const size_t o_chg = take(4), o_rb = take(L);
+    const size_t o_chg = take(4), o_steps = take(4), o_rb = take(L);
     const size_t total = o + 8;
     e = hipMalloc((void **)&pl->block, total);
     if (e != hipSuccess) { (void)hipGetLastError(); delete pl; return fail(ADT_ENOMEM, "plan tables"); }
@@ -536,6 +536,7 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     pl->counter = (int32_t *)(b + o_cnt);
     pl->group_off = (int32_t *)(b + o_grp);
     pl->changed = (int32_t *)(b + o_chg);
+    pl->steps_done = (int32_t *)(b + o_steps);
     pl->rbytes = (uint8_t *)(b + o_rb);
 
     e = hipMemset(b, 0, total);
@@ -619,7 +620,7 @@ int awp_adt_step(awp_plan *plan, const float *weights, uint8_t *packed,
     r.T = plan->T;
     r.interval = plan->interval;
     r.n_bits = plan->n_bits;
-    r.is_first = plan->steps == 0;
+    r.steps_done = plan->steps_done;
     e = adt::launch_rule(r, hs);
     if (e != hipSuccess) return fail_hip(e, "rule launch");
     ++plan->steps;

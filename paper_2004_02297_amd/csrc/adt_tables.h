@@ -128,7 +128,7 @@ struct RuleArgs {
     double T;
     int interval;
     int n_bits;
-    int is_first;
+    int32_t *steps_done;        // 0 before the first batch: that batch only records norms
 };
 
 }  // namespace adt

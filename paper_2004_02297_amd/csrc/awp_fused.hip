@@ -195,6 +195,7 @@ __global__ __launch_bounds__(kRuleBlock) void rule_kernel(const RuleArgs a) {
     __shared__ long long carry;
     __shared__ long long wave_total[kRuleWaves];
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool is_first = *a.steps_done == 0;   // read by all before thread 0 bumps it at the end
     if (tid == 0) {
         any_changed = 0;
         carry = 0;
@@ -208,7 +209,7 @@ __global__ __launch_bounds__(kRuleBlock) void rule_kernel(const RuleArgs a) {
         for (int l = l0; l < l1; ++l) sumsq += a.stats[3 * l];
         const double now = sqrt(sumsq);
         int bits = a.bits[g];
-        if (!a.is_first) {
+        if (!is_first) {
             const double prev = a.l2_prev[g];
             const double delta =
                 prev == 0.0 ? (now == 0.0 ? 0.0 : __builtin_huge_val()) : (now - prev) / prev;
@@ -258,6 +259,7 @@ __global__ __launch_bounds__(kRuleBlock) void rule_kernel(const RuleArgs a) {
         a.pack_off[a.n_layers] = carry;
         *a.packed_size = carry;
         *a.changed = any_changed;
+        *a.steps_done = 1;
     }
 }
 
