@@ -269,7 +269,7 @@ hipError_t launch_fused(const FusedArgs &a, bool write_w, hipStream_t stream) {
 }
 
 hipError_t launch_redo(const FusedArgs &a, bool write_w, hipStream_t stream) {
-    const uint32_t grid = a.n_tiles < 2048u ? a.n_tiles : 2048u;
+    const uint32_t grid = a.n_tiles < 1024u ? a.n_tiles : 1024u;
     return write_w ? launch(redo_kernel<true>, kKernelRedo, grid, kBlock, stream, a)
                    : launch(redo_kernel<false>, kKernelRedo, grid, kBlock, stream, a);
 }

@@ -131,22 +131,23 @@ __global__ __launch_bounds__(kFinalBlock) void stats_final_kernel(const StatsFin
     const uint32_t *tile_off = INLINE ? a.inl_tile_off : a.dev_tile_off;
     const int layer = (int)blockIdx.x;
     const uint32_t begin = tile_off[layer], end = tile_off[layer + 1];
-    // Thread t adds partials begin+t, begin+t+1024, ... in that order; four
+    // Thread t adds partials begin+t, begin+t+1024, ... in that order; eight
     // independent loads are in flight per round.
+    constexpr int kInFlight = 8;
     double acc = 0.0;
     uint32_t mag = 0u;
-    for (uint32_t i = begin + threadIdx.x; i < end; i += 4 * kFinalBlock) {
-        double v[4];
-        uint32_t m[4];
+    for (uint32_t i = begin + threadIdx.x; i < end; i += kInFlight * kFinalBlock) {
+        double v[kInFlight];
+        uint32_t m[kInFlight];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < kInFlight; ++j) {
             const uint32_t k = i + j * kFinalBlock;
             const bool ok = k < end;
             v[j] = ok ? a.partial_sumsq[k] : 0.0;
             m[j] = ok ? a.partial_absmax[k] : 0u;
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < kInFlight; ++j) {
             acc += v[j];
             mag = m[j] > mag ? m[j] : mag;
         }
