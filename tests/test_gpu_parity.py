@@ -347,3 +347,51 @@ def test_unpack16_full_size(adt, fmt):
     got = adt.adt_unpack16(dev(stream), ws.layer_offsets, rb, fmt)
     assert np.array_equal(got.view(torch.int16).cpu().numpy().view(np.uint16),
                           oracle.unpack16(stream, ws.layer_offsets, rb, fmt))
+
+
+# ------------------------------------------------------------------ beyond 4 GiB
+def test_offsets_beyond_four_gib(adt):
+    """Element and byte offsets that do not fit 32 bits: 1.2 G weights (4.8 GB of
+    FP32) in three layers; the stream of the middle layer starts beyond 2^32
+    bytes.  Checked against the mask closed form on the device for every
+    weight, and against the oracle on slices around each layer boundary."""
+    sizes = [(1 << 30) + 4097, 3, (1 << 27) + 11]
+    rb = np.array([4, 1, 3], dtype=np.uint8)
+    off = workloads.offsets_from_sizes(sizes)
+    N = int(off[-1])
+    g = torch.Generator(device="cuda")
+    g.manual_seed(123)
+    w = torch.randint(-(1 << 31), (1 << 31) - 1, (N,), generator=g, device="cuda",
+                      dtype=torch.int64).to(torch.int32)
+    wf = w.view(torch.float32)
+    size = adt.adt_packed_size(off, rb)
+    assert size > (1 << 32)
+    packed = adt.adt_pack(wf, off, rb)
+    back = adt.adt_unpack(packed, off, rb)
+    fused_p, fused_w = adt.adt_pack_unpack(wf, off, rb)
+    assert torch.equal(fused_p, packed)
+    pos = 0
+    for l, n in enumerate(sizes):
+        r = int(rb[l])
+        mask = MASK[r] - (1 << 32)
+        seg = slice(int(off[l]), int(off[l + 1]))
+        assert torch.equal(back[seg].view(torch.int32), w[seg] & mask), l
+        assert torch.equal(fused_w[seg].view(torch.int32), w[seg] & mask), l
+        # oracle on the first and last 5000 weights of the layer
+        for a, b in ((0, min(n, 5000)), (max(0, n - 5000), n)):
+            hw = w[seg][a:b].cpu().numpy().view(np.float32)
+            o1 = np.array([0, b - a], dtype=np.int64)
+            exp = oracle.pack(hw, o1, rb[l:l + 1])
+            got = packed[pos + a * r:pos + b * r].cpu().numpy()
+            assert np.array_equal(got, exp), (l, a, b)
+        pos += n * r
+    assert pos == size
+    del packed, back, fused_p, fused_w
+    # statistics over the same layers (values as floats may be NaN/Inf: use finite data)
+    w.copy_((torch.randn(N, generator=g, device="cuda") * 0.01).view(torch.int32))
+    st = adt.awp_layer_stats(wf, off).cpu().numpy()
+    for l in range(3):
+        seg = wf[int(off[l]):int(off[l + 1])].double()
+        ref = float(torch.sum(seg * seg))
+        assert st[l, 0] == pytest.approx(ref, rel=1e-10)
+        assert st[l, 2] == float(seg.abs().max())

@@ -3,7 +3,8 @@
 VGG-16-shaped weights take 200 steps of a multiplicative random walk
 (w += N(0, (1e-3 |w|)^2), generated on the device: input generation, not part
 of the method).  Every step runs awp_layer_stats, the AWP rule, adt_pack and
-adt_unpack.  The library's rule driven by GPU statistics must take the same
+adt_unpack, and in parallel the one-call path (awp_adt_step) with its
+device-resident state.  The library's rule driven by GPU statistics must take the same
 decisions as the oracle's rule driven by oracle statistics of the same weights;
 the packed stream and the unpacked weights are compared bit for bit on every
 step where a byte count changed and on every 20th step.
@@ -44,6 +45,10 @@ def test_awp_trajectory_vgg16():
     pap = dict(T=-2e-3, interval=4000, n_bits=8)
     g_syn, o_syn = adt.AwpState(L, 8), oracle.AwpState(L, 8)
     g_pap, o_pap = adt.AwpState(L, 8), oracle.AwpState(L, 8)
+    # the same trajectory through the one-call path with device-resident state
+    plan = adt.AwpPlan(off, syn["T"], syn["interval"], syn["n_bits"])
+    plan_packed = torch.empty(4 * N, dtype=torch.uint8, device="cuda")
+    plan_back = torch.empty_like(w)
 
     prev_rb = None
     changes = 0
@@ -72,6 +77,12 @@ def test_awp_trajectory_vgg16():
         rb_p = adt.awp_update(g_pap, g_stats[:, 1], **pap)
         assert np.array_equal(rb_p, oracle.awp_update(o_pap, o_stats[:, 1], **pap))
 
+        plan.step(w, plan_packed, plan_back)
+        pst = plan.read()
+        assert np.array_equal(pst["bytes"], orb), f"plan, step {step}"
+        assert np.array_equal(pst["bits"], o_syn.bits) and np.array_equal(pst["counter"], o_syn.counter)
+        np.testing.assert_allclose(pst["stats"], o_stats, rtol=1e-10, atol=0.0)
+
         changed = prev_rb is not None and not np.array_equal(rb, prev_rb)
         changes += int(changed)
         size = adt.adt_packed_size(off, rb)
@@ -83,6 +94,9 @@ def test_awp_trajectory_vgg16():
             assert np.array_equal(packed[:size].cpu().numpy(), exp_stream), f"step {step}"
             assert np.array_equal(back.view(torch.int32).cpu().numpy(),
                                   oracle.unpack(exp_stream, off, rb).view(np.int32)), f"step {step}"
+            assert pst["packed_size"] == size
+            assert torch.equal(plan_packed[:size], packed[:size]), f"plan stream, step {step}"
+            assert torch.equal(plan_back.view(torch.int32), back.view(torch.int32)), f"step {step}"
             checked += 1
         prev_rb = rb
 
