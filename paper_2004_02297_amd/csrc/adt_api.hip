@@ -269,7 +269,9 @@ int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
     elem_off[n_layers] = off[n_layers];
     pack_off[n_layers] = p;
     a.packed_size = p;
-    rc = build_tile_off(off, n_layers, adt::kBlockTile, tile_off);
+    const bool unpack_dir = dir == kUnpack || dir == kUnpackBf16 || dir == kUnpackFp16;
+    rc = build_tile_off(off, n_layers, unpack_dir ? adt::kUnpackBlockTile : adt::kBlockTile,
+                        tile_off);
     if (rc) return rc;
     const uint32_t n_tiles = tile_off[n_layers];
 

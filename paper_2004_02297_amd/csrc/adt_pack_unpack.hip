@@ -4,7 +4,7 @@
 // Work decomposition.  A wavefront owns a "wave tile" of 1024 consecutive
 // weights of one layer; four wave tiles make a block tile.  A wave moves its
 // tile in three steps and never talks to another wave, so no block barrier is
-// needed:
+// needed (unpack even runs one wave per block):
 //   pack   : 4 coalesced 128-bit loads per lane of FP32 words
 //            -> keep the top r bytes of every word in registers
 //            -> write the r-byte stream to the wave's LDS slice
@@ -50,11 +50,11 @@ __global__ __launch_bounds__(kBlock) void pack_kernel(const PackArgs a) {
 }
 
 template <bool INLINE, int OUT>
-__global__ __launch_bounds__(kBlock) void unpack_kernel(const PackArgs a) {
-    __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
+__global__ __launch_bounds__(kUnpackWaves * kWave) void unpack_kernel(const PackArgs a) {
+    __shared__ __attribute__((aligned(16))) uint32_t smem[kUnpackWaves][kWaveLdsDw];
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
-    const TileRef t = locate<INLINE>(a, blockIdx.x, wave);
+    const TileRef t = locate<INLINE, kUnpackWaves>(a, blockIdx.x, wave);
     if (t.len == 0) return;
     const uint8_t *src = a.packed + t.byte;
     // a.weights is the output buffer here: FP32 words or 16-bit elements
@@ -89,8 +89,8 @@ hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
         k = out_format == kOutFp32   ? unpack_kernel<false, kOutFp32>
             : out_format == kOutBf16 ? unpack_kernel<false, kOutBf16>
                                      : unpack_kernel<false, kOutFp16>;
-    return launch(k, out_format == kOutFp32 ? kKernelUnpack : kKernelUnpack16, n_tiles, kBlock,
-                  stream, a);
+    return launch(k, out_format == kOutFp32 ? kKernelUnpack : kKernelUnpack16, n_tiles,
+                  kUnpackWaves * kWave, stream, a);
 }
 
 }  // namespace adt

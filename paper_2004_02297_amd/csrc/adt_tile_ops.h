@@ -354,7 +354,7 @@ struct TileRef {
     int r;
 };
 
-template <bool INLINE>
+template <bool INLINE, int WAVES = kWavesPerBlock>
 __device__ __forceinline__ TileRef locate(const PackArgs &a, uint32_t block, int wave) {
     const uint32_t *tile_off = INLINE ? a.inl.tile_off : a.dev.tile_off;
     const int64_t *elem_off = INLINE ? a.inl.elem_off : a.dev.elem_off;
@@ -367,7 +367,7 @@ __device__ __forceinline__ TileRef locate(const PackArgs &a, uint32_t block, int
     }
     const int64_t e_begin = elem_off[lo];
     const int64_t n = elem_off[lo + 1] - e_begin;
-    const int64_t first = (int64_t)(block - tile_off[lo]) * kBlockTile +
+    const int64_t first = (int64_t)(block - tile_off[lo]) * (WAVES * kWaveTile) +
                           (int64_t)wave * kWaveTile;
     TileRef t;
     t.r = rbytes[lo];
