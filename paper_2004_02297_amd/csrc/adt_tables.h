@@ -27,8 +27,8 @@ constexpr int kBlockTile = kWaveTile * kWavesPerBlock;   // 4096 weights per blo
 constexpr int kUnpackWaves = 1;
 constexpr int kUnpackBlockTile = kWaveTile * kUnpackWaves;
 
-// Statistics kernel: 16 128-bit loads per lane, 16384 weights per block.
-constexpr int kStatsLoadsPerLane = 16;
+// Statistics kernel: 8 128-bit loads per lane, 8192 weights per block.
+constexpr int kStatsLoadsPerLane = 8;
 constexpr int kStatsTile = kBlock * kStatsLoadsPerLane * 4;
 
 constexpr int kInlineLayers = 128;

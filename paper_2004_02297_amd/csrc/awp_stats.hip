@@ -3,7 +3,7 @@
 //
 // Two launches for all layers together:
 //   1. partial kernel: the grid is the concatenation of every layer's tiles
-//      of 16384 weights.  A lane issues 128-bit loads (nontemporal: each
+//      of 8192 weights.  A lane issues 128-bit loads (nontemporal: each
 //      weight is read once), squares in double
 //      precision (the square of a binary32 value is exact in binary64) and
 //      keeps four running sums; a wave combines its lanes with xor-shuffles,
