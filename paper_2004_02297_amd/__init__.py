@@ -5,6 +5,7 @@ PyTorch is used for device memory and streams only; every step of the method
 on the weights runs in the library's gfx950 kernels.  There is no CPU fallback:
 if the library is missing, loading fails.
 """
+from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
     AWP_NSTATS, AdtError, AwpPlan, AwpState, adt_pack, adt_pack_unpack, adt_packed_size, adt_unpack16,
     adt_unpack,

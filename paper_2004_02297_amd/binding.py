@@ -14,7 +14,7 @@ import numpy as np
 from . import _build
 
 AWP_NSTATS = 3
-ADT_NKERNELS = 8
+ADT_NKERNELS = 9
 _lib = None
 
 

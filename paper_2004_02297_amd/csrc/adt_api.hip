@@ -822,6 +822,17 @@ int adt_shutdown(void) {
     }
     g_state.clear();
     if (have) (void)hipSetDevice(saved);
+    {
+        std::lock_guard<std::mutex> tlock(g_timing_mu);
+        g_timing_on = false;
+        for (const TimedLaunch &t : g_timed) g_spare.emplace_back(t.start, t.stop);
+        g_timed.clear();
+        for (auto &ev : g_spare) {
+            (void)hipEventDestroy(ev.first);
+            (void)hipEventDestroy(ev.second);
+        }
+        g_spare.clear();
+    }
     return ADT_OK;
 }
 

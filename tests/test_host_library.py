@@ -144,3 +144,26 @@ def test_group_helpers_match_oracle(adt):
         adt.awp_group_norms(st, np.array([0, 3, 2, 7], np.int32))
     with pytest.raises(adt.AdtError):
         adt.awp_group_norms(st, np.array([1, 7], np.int32))
+
+
+def test_timing_api_without_launches(adt):
+    adt.adt_timing_enable(True)
+    adt.adt_timing_enable(False)
+    t = adt.adt_timing_read()
+    lib = adt.load_library()
+    names = [lib.adt_kernel_name(k).decode() for k in range(adt.binding.ADT_NKERNELS)]
+    assert len(set(names)) == len(names) and "" not in names
+    assert lib.adt_kernel_name(adt.binding.ADT_NKERNELS) == b"" and lib.adt_kernel_name(-1) == b""
+    assert set(t) == set(names)
+    assert all(v["launches"] == 0 and v["total_ms"] == 0.0 for v in t.values())
+
+
+def test_plan_create_validates_before_touching_the_gpu(adt):
+    with pytest.raises(adt.AdtError):
+        adt.AwpPlan(np.array([0, 5, 3]), 0.0, 10)                 # decreasing offsets
+    with pytest.raises(adt.AdtError):
+        adt.AwpPlan(np.array([0, 5]), 0.0, 0)                     # interval < 1
+    with pytest.raises(adt.AdtError):
+        adt.AwpPlan(np.array([0, 5, 9]), 0.0, 1, group_offsets=np.array([0, 1]))   # groups end early
+    with pytest.raises(adt.AdtError):
+        adt.AwpPlan(np.array([0, 5]), 0.0, 1, init_bits=np.array([0], np.int32))
