@@ -11,6 +11,9 @@ pass are timed, each over its own K steps after W warm-up steps:
   three calls (reported under "three_call_path"): awp_layer_stats -> copy of
               L x 3 doubles to the host -> awp_update on the host -> adt_pack
               -> adt_unpack.
+  plan, bf16  (reported under "plan_bf16_out"; an extension, not the headline):
+              awp_adt_step16 — the same pass with the truncated weights
+              written as bfloat16 instead of FP32.
 
 Prints ONE JSON line.  `value` is FP32 weight bytes through the whole pass per
 second (4 N / step time).  Kernel durations are the dispatches' own begin / end
@@ -145,8 +148,9 @@ def main() -> int:
                     help="lower bound on the CPU-oracle timing loop (0 = skip)")
     ap.add_argument("--prime", type=int, default=150,
                     help="untimed passes before the first warm-up (see PRIME_STEPS below)")
-    ap.add_argument("--paths", default="plan,calls",
-                    help="which implementations to time: plan, calls or plan,calls")
+    ap.add_argument("--paths", default="plan,calls,plan16",
+                    help="implementations to time, first one is the headline: plan, calls, "
+                         "plan16 (comma separated)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed regions, run one plain device copy of the weight "
                          "buffer (4N bytes read, 4N written): the known-size kernel that "
@@ -163,8 +167,10 @@ def main() -> int:
               "path); run with --gpus 1", file=sys.stderr)
         return 2
     paths = [p for p in args.paths.split(",") if p]
-    if not paths or any(p not in ("plan", "calls") for p in paths):
-        print("bench.py: --paths takes plan, calls or plan,calls", file=sys.stderr)
+    if not paths or any(p not in ("plan", "calls", "plan16") for p in paths) \
+            or paths[0] == "plan16":
+        print("bench.py: --paths takes plan, calls, plan16; the first must be plan or calls",
+              file=sys.stderr)
         return 2
 
     import torch
@@ -310,6 +316,19 @@ def main() -> int:
                          "algorithmic_bytes_per_launch": bytes_pack,
                          "traffic": recorded_traffic(dom, args.workload)}}
 
+    if "plan16" in paths:
+        plan16 = adt.AwpPlan(off, T, INTERVAL, N_BITS, init_bits=start_bits)
+        w_out16 = torch.empty(N, dtype=torch.bfloat16, device="cuda")
+        ms, timing = timed_region(lambda: plan16.step(w, packed, w_out16), PRIME_STEPS)
+        assert np.array_equal(plan16.read()["bytes"], target_bytes), "AWP state drifted"
+        bytes16 = float(np.sum(sizes * (6 + rsum)))            # read W, write stream + bf16 W'
+        k16 = kern(timing, ["fused_kernel"], bytes16)
+        report["plan16"] = {
+            "value": round(4.0 * N / ms / 1e6, 2), "ms_per_step": round(ms, 5),
+            "fused_kernel": k16, "algorithmic_bytes_per_launch": bytes16}
+        plan16.close()
+        del w_out16
+
     if args.calibrate_copy:
         w_out.copy_(w)
         torch.cuda.synchronize()
@@ -340,8 +359,9 @@ def main() -> int:
     for k, v in head.items():
         if k not in ("value", "ms_per_step", "roofline"):
             result[k] = v
-    if len(paths) > 1:
-        result["three_call_path" if paths[1] == "calls" else "plan_path"] = report[paths[1]]
+    names = {"calls": "three_call_path", "plan": "plan_path", "plan16": "plan_bf16_out"}
+    for p in paths[1:]:
+        result[names[p]] = report[p]
 
     if args.cpu_seconds > 0:
         import oracle

@@ -186,6 +186,11 @@ int awp_plan_create(const int64_t *layer_offsets, int n_layers, const int32_t *i
                     double T, int interval, int n_bits, awp_plan **plan_out);
 int awp_adt_step(awp_plan *plan, const float *weights, uint8_t *packed,
                  int64_t packed_capacity, float *weights_out, adt_stream_t stream);
+/* awp_adt_step with the truncated weights written in a 16-bit format (see
+ * adt_unpack16): weights_out holds N 16-bit elements, 2-byte aligned. */
+int awp_adt_step16(awp_plan *plan, const float *weights, uint8_t *packed,
+                   int64_t packed_capacity, uint16_t *weights_out, int format,
+                   adt_stream_t stream);
 int awp_plan_read(awp_plan *plan, double *stats, int32_t *bits, int32_t *counter,
                   uint8_t *bytes, int64_t *packed_size);
 int awp_plan_destroy(awp_plan *plan);

@@ -78,6 +78,8 @@ def load_library():
     lib.awp_expand_group_bytes.argtypes = [P, P, I, P]
     lib.awp_adt_step.restype = I
     lib.awp_adt_step.argtypes = [P, P, P, I64, P, P]
+    lib.awp_adt_step16.restype = I
+    lib.awp_adt_step16.argtypes = [P, P, P, I64, P, I, P]
     lib.awp_plan_read.restype = I
     lib.awp_plan_read.argtypes = [P, P, P, P, P, P]
     lib.awp_plan_destroy.restype = I
@@ -316,12 +318,21 @@ class AwpPlan:
             raise ValueError("weights size does not match the plan")
         o = None
         if weights_out is not None:
-            o = _dev_tensor(weights_out, torch.float32, "weights_out")
+            if not isinstance(weights_out, torch.Tensor) or \
+                    weights_out.dtype not in (torch.float32, torch.bfloat16, torch.float16):
+                raise TypeError("weights_out must be a float32, bfloat16 or float16 tensor")
+            o = _dev_tensor(weights_out, weights_out.dtype, "weights_out")
             if o.numel() != self.n_weights:
                 raise ValueError("weights_out size does not match the plan")
-        _check(self._lib.awp_adt_step(self._h, w.data_ptr() or None, p.data_ptr() or None,
-                                      p.numel(), None if o is None else (o.data_ptr() or None),
-                                      _stream(stream)))
+        optr = None if o is None else (o.data_ptr() or None)
+        if o is not None and o.dtype != torch.float32:
+            # awp_adt_step16: truncated weights in a 16-bit format
+            code = 1 if o.dtype == torch.bfloat16 else 2
+            _check(self._lib.awp_adt_step16(self._h, w.data_ptr() or None, p.data_ptr() or None,
+                                            p.numel(), optr, code, _stream(stream)))
+        else:
+            _check(self._lib.awp_adt_step(self._h, w.data_ptr() or None, p.data_ptr() or None,
+                                          p.numel(), optr, _stream(stream)))
 
     def read(self) -> dict:
         """awp_plan_read: waits for the enqueued steps, returns the state."""

@@ -26,8 +26,8 @@ hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
 hipError_t launch_stats(const StatsArgs &a, const StatsFinalArgs &f, uint32_t n_tiles,
                         bool inline_table, hipStream_t stream);
 hipError_t launch_stats_final(const StatsFinalArgs &f, bool inline_table, hipStream_t stream);
-hipError_t launch_fused(const FusedArgs &a, bool write_w, hipStream_t stream);
-hipError_t launch_redo(const FusedArgs &a, bool write_w, hipStream_t stream);
+hipError_t launch_fused(const FusedArgs &a, int out_format, hipStream_t stream);
+hipError_t launch_redo(const FusedArgs &a, int out_format, hipStream_t stream);
 hipError_t launch_rule(const RuleArgs &a, hipStream_t stream);
 hipError_t launch_pack_unpack(const PackUnpackArgs &a, uint32_t n_tiles, bool inline_table,
                               hipStream_t stream);
@@ -560,16 +560,38 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     return ADT_OK;
 }
 
+namespace {
+int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t packed_capacity,
+              void *weights_out, int out_format, adt_stream_t stream);
+}
+
 int awp_adt_step(awp_plan *plan, const float *weights, uint8_t *packed,
                  int64_t packed_capacity, float *weights_out, adt_stream_t stream) {
+    return plan_step(plan, weights, packed, packed_capacity, weights_out,
+                     weights_out ? adt::kOutFp32 : -1, stream);
+}
+
+int awp_adt_step16(awp_plan *plan, const float *weights, uint8_t *packed,
+                   int64_t packed_capacity, uint16_t *weights_out, int format,
+                   adt_stream_t stream) {
+    if (format != ADT_OUT_BF16 && format != ADT_OUT_FP16)
+        return fail(ADT_EINVAL, "format must be ADT_OUT_BF16 or ADT_OUT_FP16");
+    if (!weights_out) return fail(ADT_EINVAL, "weights_out is null");
+    return plan_step(plan, weights, packed, packed_capacity, weights_out, format, stream);
+}
+
+namespace {
+int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t packed_capacity,
+              void *weights_out, int out_format, adt_stream_t stream) {
     if (!plan) return fail(ADT_EINVAL, "plan is null");
     hipStream_t hs = (hipStream_t)stream;
     plan->last_stream = hs;
     if (plan->n_layers == 0) return ADT_OK;
     if (plan->n > 0) {
         if (!weights || !packed) return fail(ADT_EINVAL, "null device pointer");
-        if (((uintptr_t)weights | (uintptr_t)weights_out) & 3u)
-            return fail(ADT_EALIGN, "FP32 buffer is not 4-byte aligned");
+        const bool out16 = out_format == adt::kOutBf16 || out_format == adt::kOutFp16;
+        if (((uintptr_t)weights & 3u) || ((uintptr_t)weights_out & (out16 ? 1u : 3u)))
+            return fail(ADT_EALIGN, "weight buffer is not aligned to its element size");
         if (packed_capacity < 4 * plan->n)
             return fail(ADT_EINVAL, "packed_capacity must be at least 4 bytes per weight");
     }
@@ -581,7 +603,7 @@ int awp_adt_step(awp_plan *plan, const float *weights, uint8_t *packed,
     adt::FusedArgs a;
     a.weights = (const uint32_t *)weights;
     a.packed = packed;
-    a.weights_out = (uint32_t *)weights_out;
+    a.weights_out = weights_out;
     a.elem_off = plan->elem_off;
     a.pack_off = plan->pack_off;
     a.tile_off = plan->tile_off;
@@ -591,10 +613,9 @@ int awp_adt_step(awp_plan *plan, const float *weights, uint8_t *packed,
     a.changed = plan->changed;
     a.n_layers = plan->n_layers;
     a.n_tiles = plan->n_tiles;
-    const bool write_w = weights_out != nullptr;
 
     if (plan->n_tiles > 0) {
-        e = adt::launch_fused(a, write_w, hs);
+        e = adt::launch_fused(a, out_format, hs);
         if (e != hipSuccess) return fail_hip(e, "fused launch");
     }
     adt::StatsFinalArgs f;
@@ -627,11 +648,12 @@ int awp_adt_step(awp_plan *plan, const float *weights, uint8_t *packed,
     if (e != hipSuccess) return fail_hip(e, "rule launch");
     ++plan->steps;
     if (plan->n_tiles > 0) {
-        e = adt::launch_redo(a, write_w, hs);
+        e = adt::launch_redo(a, out_format, hs);
         if (e != hipSuccess) return fail_hip(e, "redo launch");
     }
     return ADT_OK;
 }
+}  // namespace
 
 int awp_plan_read(awp_plan *plan, double *stats, int32_t *bits, int32_t *counter,
                   uint8_t *bytes, int64_t *packed_size) {

@@ -106,7 +106,7 @@ struct AblationArgs {
 struct FusedArgs {
     const uint32_t *weights;
     uint8_t *packed;
-    uint32_t *weights_out;      // may be null when the truncated copy is not wanted
+    void *weights_out;          // FP32 words or 16-bit elements; null: no truncated copy
     const int64_t *elem_off;
     const int64_t *pack_off;
     const uint32_t *tile_off;

@@ -51,29 +51,25 @@ __device__ __forceinline__ void square_add(uint32_t bits, double &acc, uint32_t 
     mag = m > mag ? m : mag;            // NaN patterns order above infinity
 }
 
-// Truncated words of a loaded wave tile -> FP32 output (what unpack returns).
-template <int R>
+// Truncated words of a loaded wave tile -> output weights (what unpack, or
+// unpack to a 16-bit format, returns).  dst: the tile's first output element.
+constexpr int kOutNone = -1;
+template <int R, int OUT>
 __device__ __forceinline__ void store_truncated(const u32x4 (&v)[kChunksPerLane],
-                                                uint32_t *__restrict__ dst, int len, int lane) {
+                                                void *__restrict__ dst, int len, int lane) {
     const uint32_t mask = R == 4 ? 0xFFFFFFFFu : (0xFFFFFFFFu << (8 * (4 - R)));
+    const bool dst_dw = ((uintptr_t)dst & 3u) == 0;       // wave uniform
 #pragma unroll
     for (int j = 0; j < kChunksPerLane; ++j) {
         const int e0 = 4 * (j * kWave + lane);
-        const u32x4 u = v[j] & mask;
-        if (e0 + 4 <= len) {
-            store_fp32x4(dst + e0, u);
-        } else {
-            if (e0 < len) dst[e0] = u.x;
-            if (e0 + 1 < len) dst[e0 + 1] = u.y;
-            if (e0 + 2 < len) dst[e0 + 2] = u.z;
-        }
+        if (e0 < len) store_unpacked<OUT>(dst, e0, len, v[j] & mask, dst_dw);
     }
 }
 
-template <int R, bool STATS, bool WRITE_W>
+template <int R, bool STATS, int OUT>
 __device__ __forceinline__ void fused_wave_tile(const uint32_t *__restrict__ src,
                                                 uint8_t *__restrict__ stream,
-                                                uint32_t *__restrict__ wout, int len,
+                                                void *__restrict__ wout, int len,
                                                 uint32_t *lds, int lane, double &sum,
                                                 uint32_t &mag) {
     u32x4 v[kChunksPerLane];
@@ -89,11 +85,11 @@ __device__ __forceinline__ void fused_wave_tile(const uint32_t *__restrict__ src
         }
         sum = (a0 + a1) + (a2 + a3);
     }
-    if (WRITE_W) store_truncated<R>(v, wout, len, lane);
+    if (OUT != kOutNone) store_truncated<R, OUT>(v, wout, len, lane);
     stream_out_wave_tile<R>(v, stream, len, lds, lane);
 }
 
-template <bool STATS, bool WRITE_W>
+template <bool STATS, int OUT>
 __device__ __forceinline__ void fused_block_tile(const FusedArgs &a, uint32_t tile, int wave,
                                                  int lane, uint32_t *lds, double &sum,
                                                  uint32_t &mag) {
@@ -111,17 +107,19 @@ __device__ __forceinline__ void fused_block_tile(const FusedArgs &a, uint32_t ti
     const int r = __builtin_amdgcn_readfirstlane((int)a.rbytes[lo]);
     const uint32_t *src = a.weights + e_begin + first;
     uint8_t *stream = a.packed + a.pack_off[lo] + first * r;
-    uint32_t *wout = WRITE_W ? a.weights_out + e_begin + first : nullptr;
+    void *wout = OUT == kOutNone ? nullptr
+                 : OUT == kOutFp32 ? (void *)((uint32_t *)a.weights_out + e_begin + first)
+                                   : (void *)((uint16_t *)a.weights_out + e_begin + first);
     switch (r) {
-        case 1: fused_wave_tile<1, STATS, WRITE_W>(src, stream, wout, len, lds, lane, sum, mag); break;
-        case 2: fused_wave_tile<2, STATS, WRITE_W>(src, stream, wout, len, lds, lane, sum, mag); break;
-        case 3: fused_wave_tile<3, STATS, WRITE_W>(src, stream, wout, len, lds, lane, sum, mag); break;
-        default: fused_wave_tile<4, STATS, WRITE_W>(src, stream, wout, len, lds, lane, sum, mag); break;
+        case 1: fused_wave_tile<1, STATS, OUT>(src, stream, wout, len, lds, lane, sum, mag); break;
+        case 2: fused_wave_tile<2, STATS, OUT>(src, stream, wout, len, lds, lane, sum, mag); break;
+        case 3: fused_wave_tile<3, STATS, OUT>(src, stream, wout, len, lds, lane, sum, mag); break;
+        default: fused_wave_tile<4, STATS, OUT>(src, stream, wout, len, lds, lane, sum, mag); break;
     }
 }
 
 // Speculative pass: one block tile (4096 weights) per block, statistics on.
-template <bool WRITE_W>
+template <int OUT>
 __global__ __launch_bounds__(kBlock) void fused_kernel(const FusedArgs a) {
     __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
     __shared__ double wsum[kWavesPerBlock];
@@ -130,7 +128,7 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(const FusedArgs a) {
     const int lane = (int)(threadIdx.x & 63);
     double sum = 0.0;
     uint32_t mag = 0u;
-    fused_block_tile<true, WRITE_W>(a, blockIdx.x, wave, lane, smem[wave], sum, mag);
+    fused_block_tile<true, OUT>(a, blockIdx.x, wave, lane, smem[wave], sum, mag);
     sum = fused_wave_sum(sum);
     mag = fused_wave_max(mag);
     if (lane == 0) {
@@ -148,7 +146,7 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(const FusedArgs a) {
 }
 
 // Redo pass: persistent grid; does nothing unless the rule changed a byte count.
-template <bool WRITE_W>
+template <int OUT>
 __global__ __launch_bounds__(kBlock) void redo_kernel(const FusedArgs a) {
     __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
     if (*a.changed == 0) return;
@@ -157,7 +155,7 @@ __global__ __launch_bounds__(kBlock) void redo_kernel(const FusedArgs a) {
     for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
         double sum = 0.0;
         uint32_t mag = 0u;
-        fused_block_tile<false, WRITE_W>(a, tile, wave, lane, smem[wave], sum, mag);
+        fused_block_tile<false, OUT>(a, tile, wave, lane, smem[wave], sum, mag);
         wave_lds_sync();     // the slice is reused by the next tile
     }
 }
@@ -179,10 +177,10 @@ __global__ __launch_bounds__(kBlock) void pack_unpack_kernel(const PackUnpackArg
     double sum = 0.0;
     uint32_t mag = 0u;
     switch (t.r) {
-        case 1: fused_wave_tile<1, false, true>(src, stream, wout, t.len, lds, lane, sum, mag); break;
-        case 2: fused_wave_tile<2, false, true>(src, stream, wout, t.len, lds, lane, sum, mag); break;
-        case 3: fused_wave_tile<3, false, true>(src, stream, wout, t.len, lds, lane, sum, mag); break;
-        default: fused_wave_tile<4, false, true>(src, stream, wout, t.len, lds, lane, sum, mag); break;
+        case 1: fused_wave_tile<1, false, kOutFp32>(src, stream, wout, t.len, lds, lane, sum, mag); break;
+        case 2: fused_wave_tile<2, false, kOutFp32>(src, stream, wout, t.len, lds, lane, sum, mag); break;
+        case 3: fused_wave_tile<3, false, kOutFp32>(src, stream, wout, t.len, lds, lane, sum, mag); break;
+        default: fused_wave_tile<4, false, kOutFp32>(src, stream, wout, t.len, lds, lane, sum, mag); break;
     }
 }
 
@@ -263,15 +261,22 @@ __global__ __launch_bounds__(kRuleBlock) void rule_kernel(const RuleArgs a) {
     }
 }
 
-hipError_t launch_fused(const FusedArgs &a, bool write_w, hipStream_t stream) {
-    return write_w ? launch(fused_kernel<true>, kKernelFused, a.n_tiles, kBlock, stream, a)
-                   : launch(fused_kernel<false>, kKernelFused, a.n_tiles, kBlock, stream, a);
+// out_format: kOutNone, kOutFp32, kOutBf16 or kOutFp16
+hipError_t launch_fused(const FusedArgs &a, int out_format, hipStream_t stream) {
+    void (*k)(FusedArgs) = out_format == kOutNone   ? fused_kernel<kOutNone>
+                           : out_format == kOutFp32 ? fused_kernel<kOutFp32>
+                           : out_format == kOutBf16 ? fused_kernel<kOutBf16>
+                                                    : fused_kernel<kOutFp16>;
+    return launch(k, kKernelFused, a.n_tiles, kBlock, stream, a);
 }
 
-hipError_t launch_redo(const FusedArgs &a, bool write_w, hipStream_t stream) {
+hipError_t launch_redo(const FusedArgs &a, int out_format, hipStream_t stream) {
     const uint32_t grid = a.n_tiles < 1024u ? a.n_tiles : 1024u;
-    return write_w ? launch(redo_kernel<true>, kKernelRedo, grid, kBlock, stream, a)
-                   : launch(redo_kernel<false>, kKernelRedo, grid, kBlock, stream, a);
+    void (*k)(FusedArgs) = out_format == kOutNone   ? redo_kernel<kOutNone>
+                           : out_format == kOutFp32 ? redo_kernel<kOutFp32>
+                           : out_format == kOutBf16 ? redo_kernel<kOutBf16>
+                                                    : redo_kernel<kOutFp16>;
+    return launch(k, kKernelRedo, grid, kBlock, stream, a);
 }
 
 hipError_t launch_pack_unpack(const PackUnpackArgs &a, uint32_t n_tiles, bool inline_table,

@@ -24,7 +24,7 @@ def adt():
 
 
 def run_trajectory(adt, sizes, steps, T, interval, n_bits, init_bits, seed, w_shift=0,
-                   p_shift=0, truncated=True, groups=None):
+                   p_shift=0, truncated=True, groups=None, out_dtype=torch.float32):
     rng = np.random.default_rng(seed)
     off = workloads.offsets_from_sizes(sizes)
     L, N = len(sizes), int(off[-1])
@@ -33,7 +33,7 @@ def run_trajectory(adt, sizes, steps, T, interval, n_bits, init_bits, seed, w_sh
     w = wbuf[w_shift:w_shift + N]
     pbuf = torch.full((4 * N + p_shift + 64,), 0xA5, dtype=torch.uint8, device="cuda")
     packed = pbuf[p_shift:p_shift + 4 * N]
-    obuf = torch.zeros(N + w_shift + 4, dtype=torch.float32, device="cuda")
+    obuf = torch.zeros(N + w_shift + 4, dtype=out_dtype, device="cuda")
     out = obuf[w_shift:w_shift + N] if truncated else None
 
     grp = np.arange(L + 1, dtype=np.int32) if groups is None else np.asarray(groups, np.int32)
@@ -73,9 +73,14 @@ def run_trajectory(adt, sizes, steps, T, interval, n_bits, init_bits, seed, w_sh
         hp = pbuf.cpu().numpy()
         assert np.array_equal(hp[p_shift:p_shift + exp_stream.size], exp_stream), f"step {step}"
         assert np.all(hp[:p_shift] == 0xA5) and np.all(hp[p_shift + 4 * N:] == 0xA5)
-        if truncated:
+        if truncated and out_dtype == torch.float32:
             exp_w = oracle.unpack(exp_stream, off, orb)
             assert np.array_equal(out.view(torch.int32).cpu().numpy(), exp_w.view(np.int32)), \
+                f"step {step}"
+        elif truncated:
+            fmt = "bf16" if out_dtype == torch.bfloat16 else "fp16"
+            exp16 = oracle.unpack16(exp_stream, off, orb, fmt)
+            assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), exp16), \
                 f"step {step}"
         # the three-call path gives the same stream
         p3 = adt.adt_pack(w, off, orb)
@@ -104,6 +109,14 @@ def test_plan_without_truncated_copy(adt):
     n = run_trajectory(adt, [5000, 64, 4096], steps=8, T=0.0, interval=1, n_bits=8,
                        init_bits=None, seed=3, truncated=False)
     assert n >= 1
+
+
+@pytest.mark.parametrize("out_dtype", [torch.bfloat16, torch.float16])
+def test_plan_with_16_bit_truncated_weights(adt, out_dtype):
+    sizes = [5, 4097, 1, 2049, 0, 10001, 333, 8192]
+    n = run_trajectory(adt, sizes, steps=12, T=0.0, interval=1, n_bits=8, init_bits=None,
+                       seed=7, w_shift=1, p_shift=3, out_dtype=out_dtype)
+    assert n >= 2
 
 
 def test_plan_many_layers(adt):
