@@ -41,11 +41,12 @@ __global__ __launch_bounds__(kBlock) void pack_kernel(const PackArgs a) {
     const uint32_t *src = a.weights + t.elem;
     uint8_t *dst = a.packed + t.byte;
     uint32_t *lds = smem[wave];
+    const bool nt = a.packed_size > kStreamKeepInCacheBytes;
     switch (t.r) {
-        case 1: pack_wave_tile<1>(src, dst, t.len, lds, lane); break;
-        case 2: pack_wave_tile<2>(src, dst, t.len, lds, lane); break;
-        case 3: pack_wave_tile<3>(src, dst, t.len, lds, lane); break;
-        default: pack_wave_tile<4>(src, dst, t.len, lds, lane); break;
+        case 1: pack_wave_tile<1>(src, dst, t.len, lds, lane, nt); break;
+        case 2: pack_wave_tile<2>(src, dst, t.len, lds, lane, nt); break;
+        case 3: pack_wave_tile<3>(src, dst, t.len, lds, lane, nt); break;
+        default: pack_wave_tile<4>(src, dst, t.len, lds, lane, nt); break;
     }
 }
 

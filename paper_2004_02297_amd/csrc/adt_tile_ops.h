@@ -19,12 +19,16 @@ typedef u32x4 u32x4_a4 __attribute__((aligned(4)));   // FP32 side: dword aligne
 // Cache hints.  FP32 weights are read once by pack and written once by unpack,
 // and the stream is read once by unpack: those accesses carry the nontemporal
 // hint, so their lines are not kept in L2 / Infinity Cache (on MI355X this
-// raises the sustained read rate by about 10 %).  The stream is WRITTEN with
-// ordinary stores: the consumer that follows (unpack, or a copy engine sending
-// it to a peer) then finds the most recent part of it in the Infinity Cache.
-// Measured on the statistics -> pack -> unpack pass over 138 M weights at
-// 2 bytes: 392 us without hints, 367 us with all four hints, 343 us with this
-// choice.
+// raises the sustained read rate by about 10 %).  How the stream is WRITTEN
+// depends on its size: a stream that about fits the 256 MB Infinity Cache is
+// written with ordinary stores, so that the consumer right behind it (unpack,
+// or a copy engine sending it to a peer) finds it there and its write-back
+// overlaps later work; a larger one would only thrash the cache and is written
+// nontemporal as well.  Measured on 138 M weights, whole pass through the
+// plan: 2-byte stream (264 MiB) 210 us cacheable vs 231 us nontemporal; mixed
+// stream of 295 MiB 247 vs 244 us; 3-byte stream (396 MiB) 273 vs 263 us.
+constexpr int64_t kStreamKeepInCacheBytes = (int64_t)280 << 20;
+
 #ifndef ADT_NT_FP32_LOAD
 #define ADT_NT_FP32_LOAD 1
 #endif
@@ -33,9 +37,6 @@ typedef u32x4 u32x4_a4 __attribute__((aligned(4)));   // FP32 side: dword aligne
 #endif
 #ifndef ADT_NT_STREAM_LOAD
 #define ADT_NT_STREAM_LOAD 1
-#endif
-#ifndef ADT_NT_STREAM_STORE
-#define ADT_NT_STREAM_STORE 0
 #endif
 __device__ __forceinline__ u32x4 load_fp32x4(const uint32_t *p) {
     if (ADT_NT_FP32_LOAD) return __builtin_nontemporal_load((const u32x4_a4 *)p);
@@ -49,9 +50,17 @@ __device__ __forceinline__ u32x4 load_stream16(const uint8_t *p) {   // 16-byte 
     if (ADT_NT_STREAM_LOAD) return __builtin_nontemporal_load((const u32x4 *)p);
     return *(const u32x4 *)p;
 }
-__device__ __forceinline__ void store_stream16(uint8_t *p, const u32x4 v) {
-    if (ADT_NT_STREAM_STORE) __builtin_nontemporal_store(v, (u32x4 *)p);
-    else *(u32x4 *)p = v;
+__device__ __forceinline__ void store_stream16(uint8_t *p, const u32x4 v, bool nt) {
+    if (nt) {                                   // nt is wave uniform
+        // The empty statements keep the two stores apart: without them the
+        // optimizer hoists / sinks both branches into one ordinary store and
+        // the hint is lost.
+        asm volatile("");
+        __builtin_nontemporal_store(v, (u32x4 *)p);
+        asm volatile("");
+    } else {
+        *(u32x4 *)p = v;
+    }
 }
 
 constexpr int kPadDw = 8;                              // LDS pad before / after
@@ -154,7 +163,7 @@ __device__ __forceinline__ void load_wave_tile(const uint32_t *__restrict__ src,
 template <int R>
 __device__ __forceinline__ void stream_out_wave_tile(const u32x4 (&v)[kChunksPerLane],
                                                      uint8_t *__restrict__ dst, int len,
-                                                     uint32_t *lds, int lane) {
+                                                     uint32_t *lds, int lane, bool stream_nt) {
     uint32_t *body = lds + kPadDw;
     const uint32_t s = (uint32_t)((uintptr_t)dst & 15u);   // wave uniform
 #pragma unroll
@@ -173,7 +182,7 @@ __device__ __forceinline__ void stream_out_wave_tile(const u32x4 (&v)[kChunksPer
         for (int k = 0; k < R * kChunksPerLane / 4; ++k) {
             const int q = k * kWave + lane;
             const u32x4 o = *(const u32x4 *)(body + 4 * q);
-            store_stream16(dst + 16 * q, o);
+            store_stream16(dst + 16 * q, o, stream_nt);
         }
         return;
     }
@@ -197,7 +206,7 @@ __device__ __forceinline__ void stream_out_wave_tile(const u32x4 (&v)[kChunksPer
             o.z = funnel(x3, x2, sh);
             o.w = funnel(x4, x3, sh);
             if (b0 >= 0 && b0 + 16 <= nbytes) {
-                store_stream16(dst_al + 16 * q, o);
+                store_stream16(dst_al + 16 * q, o, stream_nt);
             } else {
                 for (int t = 0; t < 16; ++t) {
                     const int bt = b0 + t;
@@ -212,10 +221,10 @@ __device__ __forceinline__ void stream_out_wave_tile(const u32x4 (&v)[kChunksPer
 template <int R>
 __device__ __forceinline__ void pack_wave_tile(const uint32_t *__restrict__ src,
                                                uint8_t *__restrict__ dst, int len,
-                                               uint32_t *lds, int lane) {
+                                               uint32_t *lds, int lane, bool stream_nt) {
     u32x4 v[kChunksPerLane];
     load_wave_tile(src, len, lane, v);
-    stream_out_wave_tile<R>(v, dst, len, lds, lane);
+    stream_out_wave_tile<R>(v, dst, len, lds, lane, stream_nt);
 }
 
 // ---------------------------------------------------------------------------

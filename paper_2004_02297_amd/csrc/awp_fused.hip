@@ -70,8 +70,8 @@ template <int R, bool STATS, int OUT>
 __device__ __forceinline__ void fused_wave_tile(const uint32_t *__restrict__ src,
                                                 uint8_t *__restrict__ stream,
                                                 void *__restrict__ wout, int len,
-                                                uint32_t *lds, int lane, double &sum,
-                                                uint32_t &mag) {
+                                                uint32_t *lds, int lane, bool stream_nt,
+                                                double &sum, uint32_t &mag) {
     u32x4 v[kChunksPerLane];
     load_wave_tile(src, len, lane, v);
     if (STATS) {
@@ -86,7 +86,7 @@ __device__ __forceinline__ void fused_wave_tile(const uint32_t *__restrict__ src
         sum = (a0 + a1) + (a2 + a3);
     }
     if (OUT != kOutNone) store_truncated<R, OUT>(v, wout, len, lane);
-    stream_out_wave_tile<R>(v, stream, len, lds, lane);
+    stream_out_wave_tile<R>(v, stream, len, lds, lane, stream_nt);
 }
 
 template <bool STATS, int OUT>
@@ -110,11 +110,12 @@ __device__ __forceinline__ void fused_block_tile(const FusedArgs &a, uint32_t ti
     void *wout = OUT == kOutNone ? nullptr
                  : OUT == kOutFp32 ? (void *)((uint32_t *)a.weights_out + e_begin + first)
                                    : (void *)((uint16_t *)a.weights_out + e_begin + first);
+    const bool nt = a.pack_off[a.n_layers] > kStreamKeepInCacheBytes;   // whole stream's size
     switch (r) {
-        case 1: fused_wave_tile<1, STATS, OUT>(src, stream, wout, len, lds, lane, sum, mag); break;
-        case 2: fused_wave_tile<2, STATS, OUT>(src, stream, wout, len, lds, lane, sum, mag); break;
-        case 3: fused_wave_tile<3, STATS, OUT>(src, stream, wout, len, lds, lane, sum, mag); break;
-        default: fused_wave_tile<4, STATS, OUT>(src, stream, wout, len, lds, lane, sum, mag); break;
+        case 1: fused_wave_tile<1, STATS, OUT>(src, stream, wout, len, lds, lane, nt, sum, mag); break;
+        case 2: fused_wave_tile<2, STATS, OUT>(src, stream, wout, len, lds, lane, nt, sum, mag); break;
+        case 3: fused_wave_tile<3, STATS, OUT>(src, stream, wout, len, lds, lane, nt, sum, mag); break;
+        default: fused_wave_tile<4, STATS, OUT>(src, stream, wout, len, lds, lane, nt, sum, mag); break;
     }
 }
 
@@ -176,11 +177,12 @@ __global__ __launch_bounds__(kBlock) void pack_unpack_kernel(const PackUnpackArg
     uint32_t *lds = smem[wave];
     double sum = 0.0;
     uint32_t mag = 0u;
+    const bool nt = a.p.packed_size > kStreamKeepInCacheBytes;
     switch (t.r) {
-        case 1: fused_wave_tile<1, false, kOutFp32>(src, stream, wout, t.len, lds, lane, sum, mag); break;
-        case 2: fused_wave_tile<2, false, kOutFp32>(src, stream, wout, t.len, lds, lane, sum, mag); break;
-        case 3: fused_wave_tile<3, false, kOutFp32>(src, stream, wout, t.len, lds, lane, sum, mag); break;
-        default: fused_wave_tile<4, false, kOutFp32>(src, stream, wout, t.len, lds, lane, sum, mag); break;
+        case 1: fused_wave_tile<1, false, kOutFp32>(src, stream, wout, t.len, lds, lane, nt, sum, mag); break;
+        case 2: fused_wave_tile<2, false, kOutFp32>(src, stream, wout, t.len, lds, lane, nt, sum, mag); break;
+        case 3: fused_wave_tile<3, false, kOutFp32>(src, stream, wout, t.len, lds, lane, nt, sum, mag); break;
+        default: fused_wave_tile<4, false, kOutFp32>(src, stream, wout, t.len, lds, lane, nt, sum, mag); break;
     }
 }
 
