@@ -29,14 +29,16 @@ enum KernelId {
 // registry) when launch timing is on.
 bool timing_events(int kernel_id, hipEvent_t *start, hipEvent_t *stop);
 
+// extra_lds: bytes of dynamic LDS the kernel does not use; they only lower
+// the number of blocks a compute unit holds at once.
 template <typename Args>
 hipError_t launch(void (*kernel)(Args), int kernel_id, uint32_t grid, int block,
-                  hipStream_t stream, const Args &args) {
+                  hipStream_t stream, const Args &args, uint32_t extra_lds = 0) {
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (timing_events(kernel_id, &e0, &e1))
-        hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(block), 0, stream, e0, e1, 0, args);
+        hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(block), extra_lds, stream, e0, e1, 0, args);
     else
-        kernel<<<dim3(grid), dim3(block), 0, stream>>>(args);
+        kernel<<<dim3(grid), dim3(block), extra_lds, stream>>>(args);
     return hipGetLastError();
 }
 

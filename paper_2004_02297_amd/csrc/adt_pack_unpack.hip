@@ -91,7 +91,7 @@ hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
             : out_format == kOutBf16 ? unpack_kernel<false, kOutBf16>
                                      : unpack_kernel<false, kOutFp16>;
     return launch(k, out_format == kOutFp32 ? kKernelUnpack : kKernelUnpack16, n_tiles,
-                  kUnpackWaves * kWave, stream, a);
+                  kUnpackWaves * kWave, stream, a, kUnpackExtraLds);
 }
 
 }  // namespace adt

@@ -31,6 +31,17 @@ constexpr int kUnpackBlockTile = kWaveTile * kUnpackWaves;
 constexpr int kStatsLoadsPerLane = 8;
 constexpr int kStatsTile = kBlock * kStatsLoadsPerLane * 4;
 
+// Waves in flight.  On MI355X a streaming kernel does not always sustain the
+// most bandwidth with the 32 waves per compute unit the hardware could hold: a
+// copy-like probe runs at 6.1 TB/s with 32 waves and 6.5 TB/s with 16, one read
+// per two writes at 5.8 vs 6.6 TB/s, a pure read at 6.9 vs 7.2 TB/s.  Unpack
+// (138 M weights at 2 bytes: 130 vs 141 us) and the statistics kernel (76.9 vs
+// 79.0 us) gain from about 16 waves; pack and the fused kernel do not, and stay
+// uncapped.  The launchers request this much dynamic LDS that no kernel
+// touches, so that a compute unit (160 KB of LDS) holds fewer blocks:
+constexpr uint32_t kUnpackExtraLds = 6144;    // 4.1 + 6 KB per 1-wave block -> 15 blocks
+constexpr uint32_t kStatsExtraLds = 36864;    // 4-wave blocks               -> 4 blocks
+
 constexpr int kInlineLayers = 128;
 
 // Layer l covers weights [elem_off[l], elem_off[l+1]), packed bytes

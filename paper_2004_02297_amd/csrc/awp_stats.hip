@@ -181,8 +181,10 @@ hipError_t launch_stats(const StatsArgs &a, const StatsFinalArgs &f, uint32_t n_
     if (n_tiles > 0) {
         hipError_t e =
             inline_table
-                ? launch(stats_partial_kernel<true>, kKernelStatsPartial, n_tiles, kBlock, stream, a)
-                : launch(stats_partial_kernel<false>, kKernelStatsPartial, n_tiles, kBlock, stream, a);
+                ? launch(stats_partial_kernel<true>, kKernelStatsPartial, n_tiles, kBlock, stream, a,
+                         kStatsExtraLds)
+                : launch(stats_partial_kernel<false>, kKernelStatsPartial, n_tiles, kBlock, stream,
+                         a, kStatsExtraLds);
         if (e != hipSuccess) return e;
     }
     return inline_table ? launch(stats_final_kernel<true>, kKernelStatsFinal, (uint32_t)f.n_layers,
