@@ -395,3 +395,34 @@ def test_offsets_beyond_four_gib(adt):
         ref = float(torch.sum(seg * seg))
         assert st[l, 0] == pytest.approx(ref, rel=1e-10)
         assert st[l, 2] == float(seg.abs().max())
+
+
+# ------------------------------------------------------------------ seeded random tables
+@pytest.mark.parametrize("seed", range(12))
+def test_random_layer_tables(adt, seed):
+    """Random numbers of layers, sizes (skewed towards tile boundaries), byte
+    counts and base misalignments; every entry point against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    L = int(rng.integers(1, 40))
+    kinds = rng.integers(0, 5, size=L)
+    sizes = np.where(kinds == 0, rng.integers(0, 8, size=L),
+             np.where(kinds == 1, 1024 * rng.integers(1, 9, size=L) + rng.integers(-2, 3, size=L),
+             np.where(kinds == 2, 4096 * rng.integers(1, 5, size=L) + rng.integers(-2, 3, size=L),
+             np.where(kinds == 3, rng.integers(1, 30000, size=L), 8192 + rng.integers(-1, 2, size=L)))))
+    sizes = np.maximum(sizes, 0)
+    rbytes = rng.integers(1, 5, size=L).astype(np.uint8)
+    off, rb, w = workloads.ragged_case(sizes, rbytes, seed=2000 + seed)
+    w_shift, p_shift = int(rng.integers(0, 4)), int(rng.integers(0, 16))
+    check_pack_unpack(adt, w, off, rb, w_shift, p_shift)
+    check_pack_unpack_fused(adt, w, off, rb, w_shift, p_shift)
+    if int(off[-1]):
+        stream = oracle.pack(w, off, rb)
+        for fmt in ("bf16", "fp16"):
+            got = adt.adt_unpack16(dev(stream), off, rb, fmt)
+            got = got.view(torch.int16).cpu().numpy().view(np.uint16)
+            exp = oracle.unpack16(stream, off, rb, fmt)
+            nan = (exp & 0x7C00 == 0x7C00) & (exp & 0x03FF != 0) if fmt == "fp16" \
+                else np.zeros(exp.shape, bool)
+            assert np.array_equal(got[~nan], exp[~nan]), fmt
+    _, _, wn = workloads.ragged_case(sizes, rbytes, seed=3000 + seed, he=True)
+    check_stats(adt, wn, off)

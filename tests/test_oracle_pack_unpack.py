@@ -242,3 +242,29 @@ def test_invalid_tables_rejected():
         oracle.pack(w, np.array([0, 5, 4]), np.array([1, 1], np.uint8))
     with pytest.raises(ValueError):
         oracle.pack(w, np.array([1, 4]), np.array([1], np.uint8))
+
+
+# ---------------------------------------------------------------- property test
+from hypothesis import given, settings, strategies as st  # noqa: E402
+
+
+@settings(max_examples=60, deadline=None)
+@given(st.lists(st.tuples(st.integers(0, 40), st.integers(1, 4)), min_size=0, max_size=8),
+       st.integers(0, 2 ** 32 - 1))
+def test_random_tables_round_trip_is_the_mask(layers, seed):
+    sizes = [n for n, _ in layers]
+    rb = np.array([r for _, r in layers], dtype=np.uint8)
+    off = workloads.offsets_from_sizes(sizes)
+    w = workloads.random_bit_patterns(int(off[-1]), seed)
+    stream = oracle.pack(w, off, rb)
+    assert stream.size == sum(n * r for n, r in layers)
+    back = oracle.unpack(stream, off, rb).view(np.uint32)
+    u = w.view(np.uint32)
+    pos = 0
+    for l, (n, r) in enumerate(layers):
+        seg = slice(int(off[l]), int(off[l + 1]))
+        assert np.array_equal(back[seg], u[seg] & np.uint32(MASK[r]))
+        # element i of the layer sits at stream bytes [pos + i r, pos + (i + 1) r)
+        img = u[seg].astype("<u4").view(np.uint8).reshape(-1, 4)[:, 4 - r:]
+        assert np.array_equal(stream[pos:pos + n * r].reshape(-1, r), img)
+        pos += n * r
