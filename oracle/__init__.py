@@ -35,11 +35,14 @@ def build(force: bool = False) -> str:
 _lib = None
 
 
-def _load():
+def _load(path=None):
+    """Load liboracle.so (or, for tests that plant mistakes in a copy of the
+    source, another build of it) and declare the C signatures."""
     global _lib
-    if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+    if _lib is None or path is not None:
+        if path is None:
+            build()
+        lib = ctypes.CDLL(path or _LIB)
         P = ctypes.c_void_p
         lib.oracle_pack.restype = ctypes.c_int64
         lib.oracle_pack.argtypes = [P, P, P, ctypes.c_int, P]
@@ -53,6 +56,8 @@ def _load():
         lib.oracle_awp_update.argtypes = [P, P, P, P, P, ctypes.c_int,
                                           ctypes.c_double, ctypes.c_int,
                                           ctypes.c_int, ctypes.c_int]
+        if path is not None:
+            return lib
         _lib = lib
     return _lib
 
