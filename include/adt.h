@@ -193,6 +193,19 @@ int awp_adt_step16(awp_plan *plan, const float *weights, uint8_t *packed,
                    adt_stream_t stream);
 int awp_plan_read(awp_plan *plan, double *stats, int32_t *bits, int32_t *counter,
                   uint8_t *bytes, int64_t *packed_size);
+/*
+ * Checkpoint / resume of a plan's AWP state (host arrays, one entry per layer,
+ * or per group for a grouped plan; any pointer may be NULL).  get waits for
+ * the steps enqueued so far; set replaces the state, recomputes the byte counts
+ * and stream offsets from `bits`, and takes effect for the next step.
+ *   l2_prev        the norms recorded by the last batch
+ *   batches_seen   0 if no batch has been processed yet (the next batch then
+ *                  only records norms), non-zero otherwise
+ */
+int awp_plan_get_state(awp_plan *plan, int32_t *bits, int32_t *counter, double *l2_prev,
+                       int32_t *batches_seen);
+int awp_plan_set_state(awp_plan *plan, const int32_t *bits, const int32_t *counter,
+                       const double *l2_prev, int32_t batches_seen);
 int awp_plan_destroy(awp_plan *plan);
 
 /*

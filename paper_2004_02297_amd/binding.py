@@ -82,6 +82,10 @@ def load_library():
     lib.awp_adt_step16.argtypes = [P, P, P, I64, P, I, P]
     lib.awp_plan_read.restype = I
     lib.awp_plan_read.argtypes = [P, P, P, P, P, P]
+    lib.awp_plan_get_state.restype = I
+    lib.awp_plan_get_state.argtypes = [P, P, P, P, P]
+    lib.awp_plan_set_state.restype = I
+    lib.awp_plan_set_state.argtypes = [P, P, P, P, ctypes.c_int32]
     lib.awp_plan_destroy.restype = I
     lib.awp_plan_destroy.argtypes = [P]
     lib.adt_ablation.restype = I
@@ -344,6 +348,25 @@ class AwpPlan:
                                        _hptr(size)))
         return {"stats": st, "bits": bits, "counter": cnt, "bytes": rb,
                 "packed_size": int(size[0])}
+
+    def get_state(self) -> dict:
+        """awp_plan_get_state: what a checkpoint has to keep."""
+        G = self.n_groups
+        bits, cnt = np.empty(G, np.int32), np.empty(G, np.int32)
+        prev, seen = np.empty(G, np.float64), np.zeros(1, np.int32)
+        _check(self._lib.awp_plan_get_state(self._h, _hptr(bits), _hptr(cnt), _hptr(prev),
+                                            _hptr(seen)))
+        return {"bits": bits, "counter": cnt, "l2_prev": prev, "batches_seen": int(seen[0])}
+
+    def set_state(self, state: dict) -> None:
+        """awp_plan_set_state: resume from get_state()'s result."""
+        bits = _host(state["bits"], np.int32)
+        cnt = _host(state["counter"], np.int32)
+        prev = _host(state["l2_prev"], np.float64)
+        if not (bits.shape == cnt.shape == prev.shape == (self.n_groups,)):
+            raise ValueError("state arrays must have one entry per group")
+        _check(self._lib.awp_plan_set_state(self._h, _hptr(bits), _hptr(cnt), _hptr(prev),
+                                            int(state["batches_seen"])))
 
     def close(self) -> None:
         if self._h is not None:

@@ -46,6 +46,8 @@ struct awp_plan {
     int interval = 0, n_bits = 0;
     int64_t steps = 0;
     hipStream_t last_stream = nullptr;
+    std::vector<int64_t> layer_sizes;   // host copy, for rebuilding the stream offsets
+    std::vector<int32_t> groups;        // host copy of group_off
     char *block = nullptr;          // one device allocation holding all of the below
     int64_t *elem_off = nullptr, *pack_off = nullptr, *packed_size = nullptr;
     uint32_t *tile_off = nullptr, *partial_absmax = nullptr;
@@ -508,6 +510,9 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     if (e != hipSuccess) { delete pl; return fail_hip(e, "hipGetDevice"); }
     pl->n_layers = n_layers;
     pl->n_groups = n_groups;
+    pl->groups = groups;
+    pl->layer_sizes.resize(L);
+    for (size_t l = 0; l < L; ++l) pl->layer_sizes[l] = layer_offsets[l + 1] - layer_offsets[l];
     pl->n = layer_offsets[n_layers];
     pl->n_tiles = tile_off[L];
     pl->T = T;
@@ -672,6 +677,60 @@ int awp_plan_read(awp_plan *plan, double *stats, int32_t *bits, int32_t *counter
     get(packed_size, plan->packed_size, 8);
     if (e == hipSuccess) e = hipStreamSynchronize(hs);
     if (e != hipSuccess) return fail_hip(e, "plan read");
+    return ADT_OK;
+}
+
+int awp_plan_get_state(awp_plan *plan, int32_t *bits, int32_t *counter, double *l2_prev,
+                       int32_t *batches_seen) {
+    if (!plan) return fail(ADT_EINVAL, "plan is null");
+    hipStream_t hs = plan->last_stream;
+    const size_t G = (size_t)plan->n_groups;
+    hipError_t e = hipSuccess;
+    auto get = [&](void *dst, const void *src, size_t n) {
+        if (dst && n && e == hipSuccess) e = hipMemcpyAsync(dst, src, n, hipMemcpyDeviceToHost, hs);
+    };
+    get(bits, plan->bits, 4 * G);
+    get(counter, plan->counter, 4 * G);
+    get(l2_prev, plan->l2_prev, 8 * G);
+    get(batches_seen, plan->steps_done, 4);
+    if (e == hipSuccess) e = hipStreamSynchronize(hs);
+    if (e != hipSuccess) return fail_hip(e, "plan get_state");
+    return ADT_OK;
+}
+
+int awp_plan_set_state(awp_plan *plan, const int32_t *bits, const int32_t *counter,
+                       const double *l2_prev, int32_t batches_seen) {
+    if (!plan) return fail(ADT_EINVAL, "plan is null");
+    const size_t G = (size_t)plan->n_groups, L = (size_t)plan->n_layers;
+    if (G && (!bits || !counter || !l2_prev)) return fail(ADT_EINVAL, "null state array");
+    std::vector<uint8_t> rb(L);
+    std::vector<int64_t> pack_off(L + 1);
+    for (size_t g = 0; g < G; ++g) {
+        if (bits[g] < 1 || bits[g] > 32) return fail(ADT_EINVAL, "bits not in 1..32");
+        if (counter[g] < 0) return fail(ADT_EINVAL, "negative counter");
+        for (int32_t l = plan->groups[g]; l < plan->groups[g + 1]; ++l)
+            rb[(size_t)l] = (uint8_t)((bits[g] + 7) >> 3);
+    }
+    int64_t p = 0;
+    for (size_t l = 0; l < L; ++l) {
+        pack_off[l] = p;
+        p += plan->layer_sizes[l] * (int64_t)rb[l];
+    }
+    pack_off[L] = p;
+    const int32_t seen = batches_seen != 0;
+    hipError_t e = hipStreamSynchronize(plan->last_stream);   // earlier steps still read the tables
+    auto put = [&](void *dst, const void *src, size_t n) {
+        if (n && e == hipSuccess) e = hipMemcpy(dst, src, n, hipMemcpyHostToDevice);
+    };
+    put(plan->bits, bits, 4 * G);
+    put(plan->counter, counter, 4 * G);
+    put(plan->l2_prev, l2_prev, 8 * G);
+    put(plan->rbytes, rb.data(), L);
+    put(plan->pack_off, pack_off.data(), 8 * (L + 1));
+    put(plan->packed_size, &p, 8);
+    put(plan->steps_done, &seen, 4);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) return fail_hip(e, "plan set_state");
     return ADT_OK;
 }
 

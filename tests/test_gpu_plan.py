@@ -243,3 +243,48 @@ def test_plan_step_replayed_from_a_hip_graph(adt):
     assert changes >= 2
     eager.close()
     graphed.close()
+
+
+def test_plan_checkpoint_and_resume(adt):
+    """A plan rebuilt from get_state() continues exactly like the original."""
+    sizes = [3000, 4096, 17, 9000, 5000]
+    groups = [0, 2, 3, 5]
+    off = workloads.offsets_from_sizes(sizes)
+    N = int(off[-1])
+    rng = np.random.default_rng(33)
+    hw = rng.standard_normal(N).astype(np.float32) * np.float32(0.05)
+    w = torch.from_numpy(hw).cuda()
+    pa, pb = (torch.zeros(4 * N, dtype=torch.uint8, device="cuda") for _ in range(2))
+    oa, ob = (torch.zeros(N, dtype=torch.float32, device="cuda") for _ in range(2))
+    a = adt.AwpPlan(off, 0.0, 2, 8, group_offsets=groups)
+    fresh = adt.AwpPlan(off, 0.0, 2, 8, group_offsets=groups).get_state()
+    assert fresh["batches_seen"] == 0 and fresh["bits"].tolist() == [8, 8, 8]
+
+    def advance():
+        scale = torch.from_numpy((1.0 + rng.choice([-0.05, 0.0, 0.05], size=N)).astype(np.float32))
+        w.mul_(scale.cuda())
+
+    for _ in range(7):
+        a.step(w, pa, oa)
+        advance()
+    saved = a.get_state()
+    assert saved["batches_seen"] == 1 and saved["bits"].max() > 8
+    b = adt.AwpPlan(off, 0.0, 2, 8, group_offsets=groups)
+    b.set_state(saved)
+    for it in range(8):
+        a.step(w, pa, oa)
+        b.step(w, pb, ob)
+        sa, sb = a.read(), b.read()
+        for k in ("bits", "counter", "bytes"):
+            assert np.array_equal(sa[k], sb[k]), (it, k)
+        n = sa["packed_size"]
+        assert n == sb["packed_size"] and torch.equal(pa[:n], pb[:n])
+        assert torch.equal(oa.view(torch.int32), ob.view(torch.int32))
+        ga, gb = a.get_state(), b.get_state()
+        assert ga["l2_prev"].tobytes() == gb["l2_prev"].tobytes()
+        advance()
+    with pytest.raises(adt.AdtError):
+        b.set_state({"bits": np.array([8, 40, 8]), "counter": np.zeros(3), "l2_prev": np.zeros(3),
+                     "batches_seen": 1})
+    a.close()
+    b.close()
