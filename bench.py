@@ -53,10 +53,16 @@ WORKLOADS = {
 }
 
 
+KERNEL_SOURCES = ("adt_tables.h", "adt_tile_ops.h", "adt_launch.h", "adt_pack_unpack.hip",
+                  "awp_stats.hip", "awp_fused.hip")
+
+
 def kernel_source_digest() -> str:
+    """Digest of the files that define the measured kernels and their launch shapes
+    (the host-side API file and the ablation kernels are not part of it)."""
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_2004_02297_amd", "csrc")
-    for f in sorted(os.listdir(d)):
+    for f in KERNEL_SOURCES:
         h.update(open(os.path.join(d, f), "rb").read())
     return h.hexdigest()[:16]
 
