@@ -35,11 +35,13 @@ constexpr int kStatsTile = kBlock * kStatsLoadsPerLane * 4;
 // most bandwidth with the 32 waves per compute unit the hardware could hold: a
 // copy-like probe runs at 6.1 TB/s with 32 waves and 6.5 TB/s with 16, one read
 // per two writes at 5.8 vs 6.6 TB/s, a pure read at 6.9 vs 7.2 TB/s.  Unpack
-// (138 M weights at 2 bytes: 130 vs 141 us) and the statistics kernel (76.9 vs
-// 79.0 us) gain from about 16 waves; pack and the fused kernel do not, and stay
+// (138 M weights, after pack, at 1 / 2 / 3 / 4 bytes: 119 / 117 / 156 / 173 us
+// with 19 waves, 124 / 122 / 163 / 176 us uncapped; 15 waves are as good from
+// 2 bytes up but cost 11 % at 1 byte) and the statistics kernel (76.9 vs
+// 79.0 us with 16 waves) gain; pack and the fused kernel do not, and stay
 // uncapped.  The launchers request this much dynamic LDS that no kernel
 // touches, so that a compute unit (160 KB of LDS) holds fewer blocks:
-constexpr uint32_t kUnpackExtraLds = 6144;    // 4.1 + 6 KB per 1-wave block -> 15 blocks
+constexpr uint32_t kUnpackExtraLds = 4096;    // 4.1 + 4 KB per 1-wave block -> 19 blocks
 constexpr uint32_t kStatsExtraLds = 36864;    // 4-wave blocks               -> 4 blocks
 
 constexpr int kInlineLayers = 128;
