@@ -38,6 +38,22 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+PROBE = os.path.join(HERE, "stream_probe")
+
+
+def build_probe(verbose: bool = False) -> str:
+    """Compile the stand-alone streaming-rate probe (csrc/stream_probe.hip)."""
+    tmp = PROBE + ".tmp.%d" % os.getpid()
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-o", tmp, os.path.join(CSRC, "stream_probe.hip")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, PROBE)
+    return PROBE
+
+
 def library_is_current() -> bool:
     if not os.path.exists(LIB):
         return False
