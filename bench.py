@@ -335,6 +335,28 @@ def main() -> int:
         plan16.close()
         del w_out16
 
+    # The single-kernel pack + unpack (adt_pack_unpack: weights read once, stream and
+    # truncated weights written), back to back, every launch timed.
+    n_pu = max(10, min(args.steps, 50))
+    for _ in range(5):
+        adt.adt_pack_unpack(w, off, target_bytes, out=packed, weights_out=w_out)
+    torch.cuda.synchronize()
+    adt.adt_timing_enable(True, n_pu)
+    adt.adt_timing_read()
+    for _ in range(n_pu):
+        adt.adt_pack_unpack(w, off, target_bytes, out=packed, weights_out=w_out)
+    torch.cuda.synchronize()
+    t_pu1 = adt.adt_timing_read()["pack_unpack_kernel"]
+    adt.adt_timing_enable(False)
+    avg_pu1 = t_pu1["total_ms"] / max(t_pu1["launches"], 1)
+    fused_pack_unpack = {
+        "entry_point": "adt_pack_unpack", "launches_timed": int(t_pu1["launches"]),
+        "avg_ms": round(avg_pu1, 5), "min_ms": round(t_pu1["min_ms"], 5),
+        "fp32_weights_gbps": round(4.0 * N / avg_pu1 / 1e6, 1),
+        "algorithmic_bytes_per_launch": bytes_fused,
+        "gbps": round(bytes_fused / avg_pu1 / 1e6, 1),
+        "hbm_frac": round(bytes_fused / avg_pu1 / 1e6 / HBM_PEAK_GBPS, 4)}
+
     if args.calibrate_copy:
         w_out.copy_(w)
         torch.cuda.synchronize()
@@ -361,6 +383,7 @@ def main() -> int:
         "kernel_timing": "dispatch begin/end timestamps on %d of the %d timed steps" % (
             n_sampled, args.steps),
         "roofline": head["roofline"],
+        "fused_pack_unpack": fused_pack_unpack,
     }
     for k, v in head.items():
         if k not in ("value", "ms_per_step", "roofline"):
