@@ -167,3 +167,48 @@ def test_plan_create_validates_before_touching_the_gpu(adt):
         adt.AwpPlan(np.array([0, 5, 9]), 0.0, 1, group_offsets=np.array([0, 1]))   # groups end early
     with pytest.raises(adt.AdtError):
         adt.AwpPlan(np.array([0, 5]), 0.0, 1, init_bits=np.array([0], np.int32))
+
+
+C_CLIENT = r"""
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+#include "adt.h"
+int main(void) {
+    /* Figure 2 of the paper: eight weights at three bytes each are 24 bytes */
+    const int64_t off[3] = {0, 8, 24};
+    const uint8_t rb[2] = {3, 2};
+    const uint8_t bad[2] = {3, 7};
+    long long size = (long long)adt_packed_size(off, rb, 2);
+    if (size != 8 * 3 + 16 * 2) { printf("size %lld\n", size); return 1; }
+    if (adt_packed_size(off, bad, 2) != ADT_EINVAL) return 2;
+    if (strcmp(adt_strerror(ADT_EINVAL), "invalid argument") != 0) return 3;
+    if (adt_last_error()[0] == 0) return 4;
+    if (adt_pack((const float *)0x1000, off, bad, 2, (uint8_t *)0x1000, 0) != ADT_EINVAL) return 5;
+    printf("ok %lld\n", size);
+    return 0;
+}
+"""
+
+
+def test_header_is_plain_c_and_a_c_program_links(adt, tmp_path):
+    """include/adt.h is the boundary: it must compile as strict C99 and as C++, and a C
+    program must be able to link the library and call it without Python in between."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "client.c"
+    src.write_text(C_CLIENT)
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc,
+                           "-c", str(src), "-o", str(tmp_path / "client.o")])
+    subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc,
+                           "-x", "c++", "-c", str(src), "-o", str(tmp_path / "client_cpp.o")])
+    lib = adt.lib_path()
+    exe = tmp_path / "client"
+    subprocess.check_call(["gcc", str(tmp_path / "client.o"), "-o", str(exe), lib,
+                           "-Wl,-rpath," + os.path.dirname(lib), "-Wl,-rpath,/opt/rocm/lib",
+                           "-L/opt/rocm/lib", "-Wl,--allow-shlib-undefined"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert out.returncode == 0 and out.stdout.strip() == "ok 56", (out.returncode, out.stdout, out.stderr)
