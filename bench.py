@@ -169,7 +169,7 @@ def main() -> int:
     if args.ablation:
         return run_ablation(args)
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no multi-GPU "
+        print("bench.py: this library runs on one GPU only (no collectives, no multi-GPU "
               "path); run with --gpus 1", file=sys.stderr)
         return 2
     paths = [p for p in args.paths.split(",") if p]
