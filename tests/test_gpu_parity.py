@@ -207,6 +207,40 @@ def test_many_layers_use_the_device_table(adt):
         check_stats(adt, w2, off2)
 
 
+def test_back_to_back_calls_with_different_large_tables(adt):
+    """Twelve pack / unpack / statistics calls with twelve different tables of more
+    than 128 layers, queued without waiting for the GPU in between: a table handed
+    to a launch must stay intact until that launch has read it, however quickly the
+    following calls come."""
+    cases = []
+    for k in range(12):
+        rng = np.random.default_rng(900 + k)
+        L = int(rng.integers(130, 400))
+        sizes = rng.integers(0, 6000, size=L)
+        rb = rng.integers(1, 5, size=L).astype(np.uint8)
+        off, rb, w = workloads.ragged_case(sizes, rb, seed=950 + k, he=True)
+        n, size = int(off[-1]), oracle.packed_size(off, rb)
+        cases.append(dict(off=off, rb=rb, w=w, dw=dev(w), n=n, size=size,
+                          p=torch.zeros(size, dtype=torch.uint8, device="cuda"),
+                          back=torch.zeros(n, dtype=torch.float32, device="cuda"),
+                          st=torch.zeros((len(rb), 3), dtype=torch.float64, device="cuda")))
+    torch.cuda.synchronize()
+    for c in cases:                       # nothing here waits for the GPU
+        adt.awp_layer_stats(c["dw"], c["off"], out=c["st"])
+        adt.adt_pack(c["dw"], c["off"], c["rb"], out=c["p"])
+        adt.adt_unpack(c["p"], c["off"], c["rb"], out=c["back"])
+    torch.cuda.synchronize()
+    for k, c in enumerate(cases):
+        exp = oracle.pack(c["w"], c["off"], c["rb"])
+        assert np.array_equal(c["p"].cpu().numpy(), exp), k
+        assert np.array_equal(c["back"].view(torch.int32).cpu().numpy(),
+                              oracle.unpack(exp, c["off"], c["rb"]).view(np.int32)), k
+        est = oracle.stats(c["w"], c["off"])
+        got = c["st"].cpu().numpy()
+        np.testing.assert_allclose(got, est, rtol=STATS_RTOL, atol=0.0)
+        np.testing.assert_array_equal(got[:, 2], est[:, 2])
+
+
 # ------------------------------------------------------------------ exhaustive bit patterns
 def test_all_bit_patterns_on_gpu(adt):
     """Every 32-bit word, every byte count: unpack(pack(w)) equals the mask
