@@ -212,3 +212,18 @@ def test_header_is_plain_c_and_a_c_program_links(adt, tmp_path):
                            "-L/opt/rocm/lib", "-Wl,--allow-shlib-undefined"])
     out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
     assert out.returncode == 0 and out.stdout.strip() == "ok 56", (out.returncode, out.stdout, out.stderr)
+
+
+def test_missing_library_fails_loudly(tmp_path, monkeypatch):
+    """No fallback: without a built library and without a compiler to build one, the
+    binding raises instead of computing anything on the CPU."""
+    import numpy as np
+    from paper_2004_02297_amd import _build, binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(_build, "LIB", str(tmp_path / "libadt_absent.so"))
+    monkeypatch.setattr(_build, "hipcc", lambda: str(tmp_path / "no_such_hipcc"))
+    with pytest.raises((OSError, RuntimeError)):
+        binding.load_library()
+    with pytest.raises((OSError, RuntimeError)):
+        binding.adt_packed_size(np.array([0, 4]), np.array([2], np.uint8))
+    assert binding._lib is None
