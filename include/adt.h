@@ -130,7 +130,14 @@ int adt_pack_unpack(const float *weights, const int64_t *layer_offsets,
  *              fixed order, so results are identical from run to run.  An
  *              empty layer gives {0, 0, 0}; a NaN weight makes all three NaN.
  * Uses per-device scratch memory owned by the library (grown on demand, kept
- * until adt_shutdown): concurrent calls on one device must share a stream.
+ * until adt_shutdown).  Calls on different streams of one device are ordered
+ * against each other by the library (a call waits, on the GPU, for the previous
+ * call's kernels before it reuses the scratch); calls from different host
+ * threads are serialised by a lock.
+ * The plan path (awp_adt_step) adds the same exact squares over tiles of 4096
+ * weights instead of 8192, so the two paths' sums agree to rounding (about
+ * 1e-15 relative), not bit for bit: an AWP decision whose delta lies within
+ * that distance of T may differ between them.
  */
 int awp_layer_stats(const float *weights, const int64_t *layer_offsets,
                     int n_layers, double *stats_out, adt_stream_t stream);
@@ -241,45 +248,11 @@ const char *adt_strerror(int status);
 const char *adt_last_error(void);
 
 /*
- * Launch timing (measurement aid, off by default).  While enabled, every
- * kernel the library launches carries the dispatch's own begin / end
- * timestamps (this costs the host about 10 us per launch, so a benchmark
- * switches it on for a sample of its steps).  adt_timing_enable(on, n) also
- * prepares event pairs for n launches ahead of time.  adt_timing_read waits
- * for the launches recorded so far, writes per-kernel totals to `out` (host,
- * ADT_NKERNELS entries, indexed as adt_kernel_name names them) and forgets
- * them.
+ * Digest of the source files this library was compiled from ("" if the build
+ * did not record one).  A loader that has the sources compares it with their
+ * digest to detect a library left over from older sources.
  */
-#define ADT_NKERNELS 9
-typedef struct adt_kernel_time {
-    int64_t launches;
-    double total_ms;
-    double min_ms;
-    double max_ms;
-} adt_kernel_time;
-int adt_timing_enable(int on, int reserve_launches);
-int adt_timing_read(adt_kernel_time *out);
-const char *adt_kernel_name(int kernel);   /* "" outside 0..ADT_NKERNELS-1 */
-
-/*
- * Ablation variants of adt_pack / adt_unpack (same arguments, same bytes; for
- * measurement of the design choices only, not for production use):
- *   ADT_ABLATION_NAIVE       one thread per weight, byte accesses on the stream
- *                            (the per-weight loops of Algorithms 2 and 5 as
- *                            written), all layers in one launch
- *   ADT_ABLATION_VEC_DIRECT  128-bit loads, register byte selection, one
- *                            4r-byte store per lane, no LDS pass (pack only;
- *                            layer starts must be 4-byte aligned)
- *   ADT_ABLATION_PER_LAYER   the production kernel, one launch per layer
- * `unpack` != 0 runs the unpack direction (then `weights` is written).
- * NAIVE and VEC_DIRECT take at most 128 layers.
- */
-#define ADT_ABLATION_NAIVE 1
-#define ADT_ABLATION_VEC_DIRECT 2
-#define ADT_ABLATION_PER_LAYER 3
-int adt_ablation(int variant, int unpack, const float *weights, const int64_t *layer_offsets,
-                 const uint8_t *bytes_per_layer, int n_layers, uint8_t *packed,
-                 adt_stream_t stream);
+const char *adt_source_digest(void);
 
 /* Frees the library's per-device scratch memory.  Optional. */
 int adt_shutdown(void);

@@ -1,0 +1,60 @@
+/*
+ * libadt measurement aids: exact per-launch kernel durations and ablation
+ * variants of the pack / unpack kernels.  Nothing here is needed to use the
+ * method; a benchmark includes this header next to adt.h.  Same conventions
+ * as adt.h (C ABI, negative adt_status on error).
+ */
+#ifndef ADT_MEASURE_H_
+#define ADT_MEASURE_H_
+
+#include "adt.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Launch timing (measurement aid, off by default).  While enabled, every
+ * kernel the library launches carries the dispatch's own begin / end
+ * timestamps (this costs the host about 10 us per launch, so a benchmark
+ * switches it on for a sample of its steps).  adt_timing_enable(on, n) also
+ * prepares event pairs for n launches ahead of time.  adt_timing_read waits
+ * for the launches recorded so far, writes per-kernel totals to `out` (host,
+ * ADT_NKERNELS entries, indexed as adt_kernel_name names them) and forgets
+ * them.
+ */
+#define ADT_NKERNELS 9
+typedef struct adt_kernel_time {
+    int64_t launches;
+    double total_ms;
+    double min_ms;
+    double max_ms;
+} adt_kernel_time;
+int adt_timing_enable(int on, int reserve_launches);
+int adt_timing_read(adt_kernel_time *out);
+const char *adt_kernel_name(int kernel);   /* "" outside 0..ADT_NKERNELS-1 */
+
+/*
+ * Ablation variants of adt_pack / adt_unpack (same arguments, same bytes; for
+ * measurement of the design choices only, not for production use):
+ *   ADT_ABLATION_NAIVE       one thread per weight, byte accesses on the stream
+ *                            (the per-weight loops of Algorithms 2 and 5 as
+ *                            written), all layers in one launch
+ *   ADT_ABLATION_VEC_DIRECT  128-bit loads, register byte selection, one
+ *                            4r-byte store per lane, no LDS pass (pack only;
+ *                            layer starts must be 4-byte aligned)
+ *   ADT_ABLATION_PER_LAYER   the production kernel, one launch per layer
+ * `unpack` != 0 runs the unpack direction (then `weights` is written).
+ * NAIVE and VEC_DIRECT take at most 128 layers.
+ */
+#define ADT_ABLATION_NAIVE 1
+#define ADT_ABLATION_VEC_DIRECT 2
+#define ADT_ABLATION_PER_LAYER 3
+int adt_ablation(int variant, int unpack, const float *weights, const int64_t *layer_offsets,
+                 const uint8_t *bytes_per_layer, int n_layers, uint8_t *packed,
+                 adt_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADT_MEASURE_H_ */

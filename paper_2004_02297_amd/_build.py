@@ -1,6 +1,7 @@
 """Builds libadt.so (gfx950) in-tree with hipcc."""
 from __future__ import annotations
 
+import hashlib
 import os
 import shutil
 import subprocess
@@ -10,7 +11,9 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadt.so")
 SOURCES = ["adt_api.hip", "adt_pack_unpack.hip", "awp_stats.hip", "awp_fused.hip",
            "adt_ablation.hip"]
-HEADERS = ["adt_tables.h", "adt_launch.h", "adt_tile_ops.h", os.path.join("..", "..", "include", "adt.h")]
+HEADERS = ["adt_tables.h", "adt_launch.h", "adt_tile_ops.h",
+           os.path.join("..", "..", "include", "adt.h"),
+           os.path.join("..", "..", "include", "adt_measure.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -27,36 +30,25 @@ def hipcc() -> str:
     return exe
 
 
+def source_digest() -> str:
+    """Digest of every file libadt.so is compiled from; the library carries the
+    digest it was built with (adt_source_digest), so a stale build is detected by
+    content, whatever the files' time stamps say."""
+    h = hashlib.sha256()
+    for f in SOURCES + HEADERS:
+        with open(os.path.join(CSRC, f), "rb") as fh:
+            h.update(fh.read())
+        h.update(b"\0")
+    return h.hexdigest()[:16]
+
+
 def build_library(verbose: bool = False) -> str:
     """Compile every HIP source for gfx950 into libadt.so (always recompiles)."""
     tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, "-o", tmp] + [os.path.join(CSRC, s) for s in SOURCES]
+    cmd = [hipcc(), *HIPCC_FLAGS, '-DADT_SOURCE_DIGEST="%s"' % source_digest(), "-o", tmp] \
+        + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
     os.replace(tmp, LIB)
     return LIB
-
-
-PROBE = os.path.join(HERE, "stream_probe")
-
-
-def build_probe(verbose: bool = False) -> str:
-    """Compile the stand-alone streaming-rate probe (csrc/stream_probe.hip)."""
-    tmp = PROBE + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-o", tmp, os.path.join(CSRC, "stream_probe.hip")]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
-    os.replace(tmp, PROBE)
-    return PROBE
-
-
-def library_is_current() -> bool:
-    if not os.path.exists(LIB):
-        return False
-    t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, s) for s in SOURCES + HEADERS]
-    return all(os.path.getmtime(d) <= t for d in deps)

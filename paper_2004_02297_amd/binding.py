@@ -34,14 +34,36 @@ def lib_path() -> str:
     return _build.LIB
 
 
+def _built_digest(path: str):
+    """adt_source_digest() of the library file at `path` (None: not exported)."""
+    lib = ctypes.CDLL(path)
+    if not hasattr(lib, "adt_source_digest"):
+        return None, lib
+    lib.adt_source_digest.restype = ctypes.c_char_p
+    lib.adt_source_digest.argtypes = []
+    return lib.adt_source_digest().decode(), lib
+
+
 def load_library():
-    """Load the in-tree libadt.so; build it only if no built library exists."""
+    """Load the in-tree libadt.so.  It is built if no built library exists, and
+    built again if the one found was compiled from other sources than the
+    tree holds now (the library carries a digest of its sources)."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(_build.LIB):
         _build.build_library()
-    lib = ctypes.CDLL(_build.LIB)
+    digest, lib = _built_digest(_build.LIB)
+    want = _build.source_digest()
+    if digest != want:
+        del lib
+        # os.replace gives the rebuilt file a new inode, so the second dlopen maps the new code
+        _build.build_library()
+        digest, lib = _built_digest(_build.LIB)
+        if digest != want:
+            raise RuntimeError("libadt.so at %s was built from other sources (digest %r, the "
+                               "tree has %r) and rebuilding did not change that"
+                               % (_build.LIB, digest, want))
     P, I, I64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
     lib.adt_packed_size.restype = I64
     lib.adt_packed_size.argtypes = [P, P, I]

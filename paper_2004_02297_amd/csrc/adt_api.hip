@@ -14,6 +14,7 @@
 #include <vector>
 
 #include "../../include/adt.h"
+#include "../../include/adt_measure.h"
 #include "adt_launch.h"
 #include "adt_tables.h"
 #include "adt_tile_ops.h"
@@ -90,6 +91,12 @@ struct DeviceState {
     int next = 0;
     void *stats_scratch = nullptr;
     size_t stats_cap = 0;
+    // The statistics scratch is shared by all calls on the device: the event
+    // marks the end of the last call that used it, and a call on another
+    // stream waits for it before it overwrites the partials.
+    hipEvent_t stats_ev = nullptr;
+    hipStream_t stats_stream = nullptr;
+    bool stats_pending = false;
 };
 
 std::mutex g_mu;
@@ -102,8 +109,18 @@ struct TimedLaunch {
 };
 std::mutex g_timing_mu;
 bool g_timing_on = false;
+constexpr size_t kMaxTimedLaunches = 1u << 16;          // launches kept until adt_timing_read
 std::vector<TimedLaunch> g_timed;                       // launches not yet read
 std::vector<std::pair<hipEvent_t, hipEvent_t>> g_spare;  // event pairs to reuse
+
+bool stream_is_capturing(hipStream_t stream) {
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &st) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return st != hipStreamCaptureStatusNone;
+}
 
 void release_slot(Slot &s) {
     if (s.pending && s.ev) (void)hipEventSynchronize(s.ev);
@@ -149,6 +166,7 @@ int acquire_slot(DeviceState &st, size_t bytes, Slot **out) {
 }
 
 size_t align8(size_t x) { return (x + 7) & ~(size_t)7; }
+
 
 // ---- validation -------------------------------------------------------------
 int check_tables(const int64_t *off, const uint8_t *rb, bool need_rb, int n_layers) {
@@ -297,9 +315,11 @@ int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
 
 }  // namespace
 
-bool adt::timing_events(int kernel_id, hipEvent_t *start, hipEvent_t *stop) {
+bool adt::timing_events(int kernel_id, hipStream_t stream, hipEvent_t *start, hipEvent_t *stop) {
     std::lock_guard<std::mutex> lock(g_timing_mu);
     if (!g_timing_on) return false;
+    if (g_timed.size() >= kMaxTimedLaunches) return false;   // unread records are bounded
+    if (stream_is_capturing(stream)) return false;
     std::pair<hipEvent_t, hipEvent_t> ev{nullptr, nullptr};
     if (!g_spare.empty()) {
         ev = g_spare.back();
@@ -428,6 +448,11 @@ int awp_layer_stats(const float *weights, const int64_t *layer_offsets, int n_la
     f.stats_out = stats_out;
     f.n_layers = n_layers;
 
+    const bool capturing = stream_is_capturing(hs);
+    if (st.stats_pending && st.stats_stream != hs && !capturing) {
+        e = hipStreamWaitEvent(hs, st.stats_ev, 0);
+        if (e != hipSuccess) return fail_hip(e, "hipStreamWaitEvent(statistics scratch)");
+    }
     if (!inl) {
         e = hipMemcpyAsync(slot->dev, slot->host, bytes, hipMemcpyHostToDevice, hs);
         if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(table)");
@@ -438,6 +463,20 @@ int awp_layer_stats(const float *weights, const int64_t *layer_offsets, int n_la
         else (void)hipStreamSynchronize(hs);
     }
     if (e != hipSuccess) return fail_hip(e, "statistics launch");
+    if (!capturing) {
+        if (!st.stats_ev &&
+            hipEventCreateWithFlags(&st.stats_ev, hipEventDisableTiming) != hipSuccess) {
+            (void)hipGetLastError();
+            st.stats_ev = nullptr;
+        }
+        if (st.stats_ev && hipEventRecord(st.stats_ev, hs) == hipSuccess) {
+            st.stats_pending = true;
+            st.stats_stream = hs;
+        } else {
+            (void)hipStreamSynchronize(hs);     // no event: fall back to waiting here
+            st.stats_pending = false;
+        }
+    }
     return ADT_OK;
 }
 
@@ -840,6 +879,11 @@ const char *adt_strerror(int status) {
 
 const char *adt_last_error(void) { return g_err.c_str(); }
 
+#ifndef ADT_SOURCE_DIGEST
+#define ADT_SOURCE_DIGEST ""
+#endif
+const char *adt_source_digest(void) { return ADT_SOURCE_DIGEST; }
+
 int adt_timing_enable(int on, int reserve_launches) {
     std::lock_guard<std::mutex> lock(g_timing_mu);
     g_timing_on = on != 0;
@@ -900,6 +944,7 @@ int adt_shutdown(void) {
         if (hipSetDevice(kv.first) != hipSuccess) continue;
         for (Slot &s : kv.second.ring) release_slot(s);
         if (kv.second.stats_scratch) (void)hipFree(kv.second.stats_scratch);
+        if (kv.second.stats_ev) (void)hipEventDestroy(kv.second.stats_ev);
     }
     g_state.clear();
     if (have) (void)hipSetDevice(saved);

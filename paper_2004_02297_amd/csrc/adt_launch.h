@@ -26,8 +26,10 @@ enum KernelId {
 };
 
 // Defined in adt_api.hip.  True (and a fresh event pair, owned by the timing
-// registry) when launch timing is on.
-bool timing_events(int kernel_id, hipEvent_t *start, hipEvent_t *stop);
+// registry) when launch timing is on and `stream` is not being captured into a
+// graph (a captured launch is an ordinary launch: timing events would never
+// complete).
+bool timing_events(int kernel_id, hipStream_t stream, hipEvent_t *start, hipEvent_t *stop);
 
 // extra_lds: bytes of dynamic LDS the kernel does not use; they only lower
 // the number of blocks a compute unit holds at once.
@@ -35,7 +37,7 @@ template <typename Args>
 hipError_t launch(void (*kernel)(Args), int kernel_id, uint32_t grid, int block,
                   hipStream_t stream, const Args &args, uint32_t extra_lds = 0) {
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (timing_events(kernel_id, &e0, &e1))
+    if (timing_events(kernel_id, stream, &e0, &e1))
         hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(block), extra_lds, stream, e0, e1, 0, args);
     else
         kernel<<<dim3(grid), dim3(block), extra_lds, stream>>>(args);

@@ -22,18 +22,23 @@ def adt():
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "adt.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b((?:adt|awp)_[a-z0-9_]+)\s*\(", text)))
+    """Every function any header under include/ declares."""
+    import glob
+    syms = set()
+    for path in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))):
+        text = re.sub(r"/\*.*?\*/", "", open(path).read(), flags=re.S)
+        syms |= set(re.findall(r"\b((?:adt|awp)_[a-z0-9_]+)\s*\(", text))
+    return sorted(syms)
 
 
 def test_header_symbols_are_exported(adt):
     syms = declared_symbols()
     assert {"adt_pack", "adt_unpack", "awp_layer_stats", "adt_packed_size", "awp_update",
-            "adt_strerror", "adt_last_error", "adt_shutdown"} <= set(syms)
+            "adt_strerror", "adt_last_error", "adt_shutdown", "adt_timing_read", "adt_ablation",
+            "adt_source_digest"} <= set(syms)
     lib = ctypes.CDLL(adt.lib_path())
     for s in syms:
-        assert hasattr(lib, s), f"{s} declared in adt.h but not exported"
+        assert hasattr(lib, s), f"{s} declared under include/ but not exported"
 
 
 def test_packed_size(adt):
@@ -227,3 +232,18 @@ def test_missing_library_fails_loudly(tmp_path, monkeypatch):
     with pytest.raises((OSError, RuntimeError)):
         binding.adt_packed_size(np.array([0, 4]), np.array([2], np.uint8))
     assert binding._lib is None
+
+
+def test_stale_library_is_rebuilt(monkeypatch, adt):
+    """A library compiled from other sources than the tree holds is not used as it
+    is: load_library() builds again (and fails loudly if that does not help)."""
+    from paper_2004_02297_amd import _build, binding
+    lib = adt.load_library()
+    assert lib.adt_source_digest().decode() == _build.source_digest()
+    calls = []
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(_build, "source_digest", lambda: "0123456789abcdef")
+    monkeypatch.setattr(_build, "build_library", lambda verbose=False: calls.append(1))
+    with pytest.raises(RuntimeError, match="built from other sources"):
+        binding.load_library()
+    assert calls == [1] and binding._lib is None
