@@ -35,6 +35,17 @@ int adt_timing_read(adt_kernel_time *out);
 const char *adt_kernel_name(int kernel);   /* "" outside 0..ADT_NKERNELS-1 */
 
 /*
+ * Size limit of the cache-friendly stream stores (tuning aid).  The kernels
+ * write a packed stream of at most this many bytes with ordinary stores, so
+ * that a consumer right behind them can find it in the last-level cache, and a
+ * larger one with nontemporal stores.  bytes >= 0 sets the limit for later
+ * calls (0: always nontemporal; INT64_MAX: never) and returns the previous
+ * value; bytes < 0 only returns the current value.  The stream's bytes are the
+ * same either way.
+ */
+int64_t adt_stream_cache_limit(int64_t bytes);
+
+/*
  * Ablation variants of adt_pack / adt_unpack (same arguments, same bytes; for
  * measurement of the design choices only, not for production use):
  *   ADT_ABLATION_NAIVE       one thread per weight, byte accesses on the stream

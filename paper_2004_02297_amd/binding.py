@@ -112,6 +112,8 @@ def load_library():
     lib.awp_plan_destroy.argtypes = [P]
     lib.adt_ablation.restype = I
     lib.adt_ablation.argtypes = [I, I, P, P, P, I, P, P]
+    lib.adt_stream_cache_limit.restype = I64
+    lib.adt_stream_cache_limit.argtypes = [I64]
     lib.adt_shutdown.restype = I
     lib.adt_shutdown.argtypes = []
     _lib = lib
@@ -301,6 +303,12 @@ def awp_update(state: AwpState, l2_now, T: float, interval: int, n_bits: int = 8
 def adt_timing_enable(on: bool, reserve_launches: int = 0) -> None:
     """adt_timing_enable: exact per-launch kernel durations on / off."""
     _check(load_library().adt_timing_enable(1 if on else 0, int(reserve_launches)))
+
+
+def adt_stream_cache_limit(nbytes: int = -1) -> int:
+    """adt_stream_cache_limit: set (nbytes >= 0) or read the size limit below which the
+    packed stream is written with cache-friendly stores; returns the previous value."""
+    return int(load_library().adt_stream_cache_limit(int(nbytes)))
 
 
 def adt_timing_read() -> dict:

@@ -7,6 +7,7 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <atomic>
 #include <map>
 #include <mutex>
 #include <new>
@@ -101,6 +102,9 @@ struct DeviceState {
 
 std::mutex g_mu;
 std::map<int, DeviceState> g_state;
+
+// Streams above this size are written with nontemporal stores (adt_tile_ops.h).
+std::atomic<int64_t> g_stream_cache_limit{adt::kStreamKeepInCacheBytes};
 
 // ---- launch timing ----------------------------------------------------------
 struct TimedLaunch {
@@ -244,6 +248,7 @@ int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
     a.weights = (const uint32_t *)weights;
     a.packed = (uint8_t *)packed;
     a.n_layers = n_layers;
+    a.stream_cache_limit = g_stream_cache_limit.load();
     a.dev = adt::DeviceTable{nullptr, nullptr, nullptr, nullptr};
     const bool inl = n_layers <= adt::kInlineLayers;
     hipStream_t hs = (hipStream_t)stream;
@@ -655,6 +660,7 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
     a.partial_sumsq = plan->partial_sumsq;
     a.partial_absmax = plan->partial_absmax;
     a.changed = plan->changed;
+    a.stream_cache_limit = g_stream_cache_limit.load();
     a.n_layers = plan->n_layers;
     a.n_tiles = plan->n_tiles;
 
@@ -883,6 +889,11 @@ const char *adt_last_error(void) { return g_err.c_str(); }
 #define ADT_SOURCE_DIGEST ""
 #endif
 const char *adt_source_digest(void) { return ADT_SOURCE_DIGEST; }
+
+int64_t adt_stream_cache_limit(int64_t bytes) {
+    if (bytes < 0) return g_stream_cache_limit.load();
+    return g_stream_cache_limit.exchange(bytes);
+}
 
 int adt_timing_enable(int on, int reserve_launches) {
     std::lock_guard<std::mutex> lock(g_timing_mu);

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kBlock) void pack_kernel(const PackArgs a) {
     const uint32_t *src = a.weights + t.elem;
     uint8_t *dst = a.packed + t.byte;
     uint32_t *lds = smem[wave];
-    const bool nt = a.packed_size > kStreamKeepInCacheBytes;
+    const bool nt = a.packed_size > a.stream_cache_limit;
     switch (t.r) {
         case 1: pack_wave_tile<1>(src, dst, t.len, lds, lane, nt); break;
         case 2: pack_wave_tile<2>(src, dst, t.len, lds, lane, nt); break;

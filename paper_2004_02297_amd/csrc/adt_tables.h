@@ -66,6 +66,7 @@ struct PackArgs {
     const uint32_t *weights;   // FP32 words, read by pack / written by unpack
     uint8_t *packed;           // dense stream
     int64_t packed_size;       // bytes in the whole stream
+    int64_t stream_cache_limit;   // streams larger than this are written nontemporal
     int n_layers;
     DeviceTable dev;           // used when n_layers > kInlineLayers
     InlineTable inl;
@@ -127,6 +128,7 @@ struct FusedArgs {
     double *partial_sumsq;      // one per block tile
     uint32_t *partial_absmax;
     const int32_t *changed;
+    int64_t stream_cache_limit;   // streams larger than this are written nontemporal
     int n_layers;
     uint32_t n_tiles;
 };

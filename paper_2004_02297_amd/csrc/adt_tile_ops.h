@@ -27,7 +27,7 @@ typedef u32x4 u32x4_a4 __attribute__((aligned(4)));   // FP32 side: dword aligne
 // nontemporal as well.  Measured on 138 M weights, whole pass through the
 // plan: 2-byte stream (264 MiB) 210 us cacheable vs 231 us nontemporal; mixed
 // stream of 295 MiB 247 vs 244 us; 3-byte stream (396 MiB) 273 vs 263 us.
-constexpr int64_t kStreamKeepInCacheBytes = (int64_t)280 << 20;
+constexpr int64_t kStreamKeepInCacheBytes = (int64_t)280 << 20;   // default of the limit
 
 #ifndef ADT_NT_FP32_LOAD
 #define ADT_NT_FP32_LOAD 1

@@ -110,7 +110,7 @@ __device__ __forceinline__ void fused_block_tile(const FusedArgs &a, uint32_t ti
     void *wout = OUT == kOutNone ? nullptr
                  : OUT == kOutFp32 ? (void *)((uint32_t *)a.weights_out + e_begin + first)
                                    : (void *)((uint16_t *)a.weights_out + e_begin + first);
-    const bool nt = a.pack_off[a.n_layers] > kStreamKeepInCacheBytes;   // whole stream's size
+    const bool nt = a.pack_off[a.n_layers] > a.stream_cache_limit;   // whole stream's size
     switch (r) {
         case 1: fused_wave_tile<1, STATS, OUT>(src, stream, wout, len, lds, lane, nt, sum, mag); break;
         case 2: fused_wave_tile<2, STATS, OUT>(src, stream, wout, len, lds, lane, nt, sum, mag); break;
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kBlock) void pack_unpack_kernel(const PackUnpackArg
     uint32_t *lds = smem[wave];
     double sum = 0.0;
     uint32_t mag = 0u;
-    const bool nt = a.p.packed_size > kStreamKeepInCacheBytes;
+    const bool nt = a.p.packed_size > a.p.stream_cache_limit;
     switch (t.r) {
         case 1: fused_wave_tile<1, false, kOutFp32>(src, stream, wout, t.len, lds, lane, nt, sum, mag); break;
         case 2: fused_wave_tile<2, false, kOutFp32>(src, stream, wout, t.len, lds, lane, nt, sum, mag); break;
