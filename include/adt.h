@@ -143,6 +143,28 @@ int awp_layer_stats(const float *weights, const int64_t *layer_offsets,
                     int n_layers, double *stats_out, adt_stream_t stream);
 
 /*
+ * awp_layer_stats for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels and bit-identical results as awp_layer_stats,
+ * but the partial sums live in a fixed array inside the library's device image
+ * (AWP_NOALLOC_MAX_TILES * 12 bytes = 1.5 MiB, held by every GPU the library
+ * runs on until the process ends) and the call never allocates or frees
+ * anything, on the host side of HIP or on the device.
+ * Limits (ADT_ERANGE beyond them, nothing launched): n_layers <= 128, and
+ * sum over layers of ceil(n_l / 8192) <= AWP_NOALLOC_MAX_TILES (about 1.07 G
+ * weights).
+ * All calls on one GPU share that array: calls that overlap in time on one GPU
+ * (different streams without ordering, or different host threads) race and
+ * give wrong statistics; order them on one stream or with events.  The array
+ * keeps the last call's partials; nothing in it needs clearing between calls.
+ * The first call on a device looks up the array's device address; make that
+ * call outside a graph capture.
+ */
+#define AWP_NOALLOC_MAX_TILES 131072
+int awp_layer_stats_noalloc(const float *weights, const int64_t *layer_offsets,
+                            int n_layers, double *stats_out, adt_stream_t stream);
+
+/*
  * One batch of the AWP rule (Section II, Algorithm 1) for all layers.  Host
  * only, no GPU; all pointers are host arrays of n_layers entries.
  *   delta = (l2_now - l2_prev) / l2_prev; if delta < T the layer's counter

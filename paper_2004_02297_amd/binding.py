@@ -77,6 +77,8 @@ def load_library():
     lib.adt_pack_unpack.argtypes = [P, P, P, I, P, P, P]
     lib.awp_layer_stats.restype = I
     lib.awp_layer_stats.argtypes = [P, P, I, P, P]
+    lib.awp_layer_stats_noalloc.restype = I
+    lib.awp_layer_stats_noalloc.argtypes = [P, P, I, P, P]
     lib.awp_update.restype = I
     lib.awp_update.argtypes = [P, P, P, P, P, I, ctypes.c_double, I, I, I]
     lib.adt_strerror.restype = ctypes.c_char_p
@@ -272,6 +274,23 @@ def awp_layer_stats(weights, layer_offsets, out=None, stream=None):
             raise ValueError("out must hold n_layers * 3 doubles")
     _check(load_library().awp_layer_stats(w.data_ptr() or None, _hptr(off), L,
                                           out.data_ptr() or None, _stream(stream)))
+    return out
+
+
+def awp_layer_stats_noalloc(weights, layer_offsets, out, stream=None):
+    """awp_layer_stats_noalloc: as awp_layer_stats, scratch in the library's fixed
+    device array; `out` (device float64[L, 3]) must be passed in, nothing is allocated."""
+    import torch
+    off = _host(layer_offsets, np.int64)
+    L = off.size - 1
+    w = _dev_tensor(weights, torch.float32, "weights")
+    if w.numel() != int(off[-1]):
+        raise ValueError("weights size does not match layer_offsets[-1]")
+    _dev_tensor(out, torch.float64, "out")
+    if out.numel() != L * AWP_NSTATS:
+        raise ValueError("out must hold n_layers * 3 doubles")
+    _check(load_library().awp_layer_stats_noalloc(w.data_ptr() or None, _hptr(off), L,
+                                                  out.data_ptr() or None, _stream(stream)))
     return out
 
 

@@ -62,6 +62,14 @@ static_assert(ADT_NKERNELS == adt::kNumKernels, "adt.h and adt_launch.h disagree
 static_assert(ADT_OUT_BF16 == adt::kOutBf16 && ADT_OUT_FP16 == adt::kOutFp16,
               "adt.h and adt_tile_ops.h disagree");
 
+// Fixed scratch of awp_layer_stats_noalloc: one double and one magnitude word
+// per statistics tile.  Every device the library runs on holds its own copy of
+// this array until the process ends; host code reaches a device's copy only
+// through the address hipGetSymbolAddress returns for it (noalloc_scratch()).
+constexpr uint32_t kNoAllocMaxTiles = AWP_NOALLOC_MAX_TILES;
+constexpr size_t kNoAllocScratchBytes = (size_t)kNoAllocMaxTiles * 12;
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
 namespace {
 
 thread_local std::string g_err;
@@ -171,6 +179,30 @@ int acquire_slot(DeviceState &st, size_t bytes, Slot **out) {
 
 size_t align8(size_t x) { return (x + 7) & ~(size_t)7; }
 
+// Device address of the current device's copy of `scratch`, looked up once per
+// device (with that device current) and kept.  No allocation.
+constexpr int kMaxDevices = 64;
+std::mutex g_noalloc_mu;
+unsigned char *g_noalloc_ptr[kMaxDevices] = {};
+
+int noalloc_scratch(unsigned char **out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(ADT_ERANGE, "device index out of range");
+    std::lock_guard<std::mutex> lock(g_noalloc_mu);
+    if (!g_noalloc_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return fail_hip(e, "hipGetSymbolAddress(scratch)");
+        }
+        g_noalloc_ptr[dev] = (unsigned char *)p;
+    }
+    *out = g_noalloc_ptr[dev];
+    return ADT_OK;
+}
 
 // ---- validation -------------------------------------------------------------
 int check_tables(const int64_t *off, const uint8_t *rb, bool need_rb, int n_layers) {
@@ -482,6 +514,53 @@ int awp_layer_stats(const float *weights, const int64_t *layer_offsets, int n_la
             st.stats_pending = false;
         }
     }
+    return ADT_OK;
+}
+
+int awp_layer_stats_noalloc(const float *weights, const int64_t *layer_offsets, int n_layers,
+                            double *stats_out, adt_stream_t stream) {
+    int rc = check_tables(layer_offsets, nullptr, false, n_layers);
+    if (rc) return rc;
+    if (n_layers == 0) return ADT_OK;
+    const int64_t n = layer_offsets[n_layers];
+    if (!stats_out) return fail(ADT_EINVAL, "stats_out is null");
+    if (n > 0 && !weights) return fail(ADT_EINVAL, "weights is null");
+    if ((uintptr_t)weights & 3u) return fail(ADT_EALIGN, "FP32 buffer is not 4-byte aligned");
+    if ((uintptr_t)stats_out & 7u) return fail(ADT_EALIGN, "stats_out is not 8-byte aligned");
+    if (n_layers > adt::kInlineLayers)
+        return fail(ADT_ERANGE, "awp_layer_stats_noalloc takes at most " +
+                                    std::to_string(adt::kInlineLayers) + " layers");
+
+    adt::StatsArgs a;
+    adt::StatsFinalArgs f;
+    a.dev_elem_off = nullptr;
+    a.dev_tile_off = nullptr;
+    f.dev_tile_off = nullptr;
+    for (int l = 0; l <= n_layers; ++l) a.inl.elem_off[l] = layer_offsets[l];
+    rc = build_tile_off(layer_offsets, n_layers, adt::kStatsTile, a.inl.tile_off);
+    if (rc) return rc;
+    const uint32_t n_tiles = a.inl.tile_off[n_layers];
+    if (n_tiles > kNoAllocMaxTiles)
+        return fail(ADT_ERANGE, "awp_layer_stats_noalloc: " + std::to_string(n_tiles) +
+                                    " tiles of 8192 weights exceed the fixed scratch of " +
+                                    std::to_string(kNoAllocMaxTiles) + " tiles");
+    memcpy(f.inl_tile_off, a.inl.tile_off, 4 * ((size_t)n_layers + 1));
+
+    unsigned char *base = nullptr;
+    rc = noalloc_scratch(&base);
+    if (rc) return rc;
+    // Nothing in the scratch has to start at zero: the partial kernel writes
+    // every entry [0, n_tiles) that the final kernel reads.
+    a.weights = (const uint32_t *)weights;
+    a.partial_sumsq = (double *)base;
+    a.partial_absmax = (uint32_t *)(base + (size_t)kNoAllocMaxTiles * 8);
+    a.n_layers = n_layers;
+    f.partial_sumsq = a.partial_sumsq;
+    f.partial_absmax = a.partial_absmax;
+    f.stats_out = stats_out;
+    f.n_layers = n_layers;
+    hipError_t e = adt::launch_stats(a, f, n_tiles, true, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "statistics launch");
     return ADT_OK;
 }
 
