@@ -23,7 +23,7 @@ extern "C" {
  * ADT_NKERNELS entries, indexed as adt_kernel_name names them) and forgets
  * them.
  */
-#define ADT_NKERNELS 9
+#define ADT_NKERNELS 10
 typedef struct adt_kernel_time {
     int64_t launches;
     double total_ms;
@@ -35,15 +35,28 @@ int adt_timing_read(adt_kernel_time *out);
 const char *adt_kernel_name(int kernel);   /* "" outside 0..ADT_NKERNELS-1 */
 
 /*
- * Size limit of the cache-friendly stream stores (tuning aid).  The kernels
- * write a packed stream of at most this many bytes with ordinary stores, so
- * that a consumer right behind them can find it in the last-level cache, and a
- * larger one with nontemporal stores.  bytes >= 0 sets the limit for later
- * calls (0: always nontemporal; INT64_MAX: never) and returns the previous
- * value; bytes < 0 only returns the current value.  The stream's bytes are the
- * same either way.
+ * Launch shape of a streaming kernel (tuning aid): wavefronts per block and a
+ * number of bytes of dynamic LDS that the kernel never touches, which lowers
+ * the number of blocks a compute unit holds at once.  kernel: the index of
+ * "pack_kernel", "unpack_kernel", "pack_unpack_kernel" or "fused_kernel"
+ * (adt_kernel_name); waves: 1 or 4 (unpack_kernel: 1), or 0 to return to the
+ * library's own choice.  Results do not depend on the shape, bit for bit.
  */
-int64_t adt_stream_cache_limit(int64_t bytes);
+int adt_launch_shape(int kernel, int waves, int extra_lds_bytes);
+
+/*
+ * Size limit of the cache-friendly stream stores (tuning aid).  A kernel writes
+ * a packed stream of at most this many bytes with ordinary stores, so that a
+ * consumer right behind it can find the stream in the last-level cache, and a
+ * larger one with nontemporal stores.  kernel: the index of "pack_kernel" (its
+ * own limit, 320 MiB by default: adt_unpack usually follows), or of
+ * "pack_unpack_kernel" / "fused_kernel" (one shared limit, 0 by default: always
+ * nontemporal).  bytes >= 0 sets the limit for later calls (INT64_MAX: never
+ * nontemporal) and returns the previous value; bytes < 0 only returns the
+ * current value; negative adt_status for another kernel.  The stream's bytes
+ * are the same either way.
+ */
+int64_t adt_stream_cache_limit(int kernel, int64_t bytes);
 
 /*
  * Ablation variants of adt_pack / adt_unpack (same arguments, same bytes; for

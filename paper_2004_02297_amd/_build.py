@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadt.so")
 SOURCES = ["adt_api.hip", "adt_pack_unpack.hip", "awp_stats.hip", "awp_fused.hip",
            "adt_ablation.hip"]
-HEADERS = ["adt_tables.h", "adt_launch.h", "adt_tile_ops.h",
+HEADERS = ["adt_tables.h", "adt_launch.h", "adt_tile_ops.h", "awp_partials.h",
            os.path.join("..", "..", "include", "adt.h"),
            os.path.join("..", "..", "include", "adt_measure.h")]
 

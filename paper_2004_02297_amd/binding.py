@@ -14,7 +14,7 @@ import numpy as np
 from . import _build
 
 AWP_NSTATS = 3
-ADT_NKERNELS = 9
+ADT_NKERNELS = 10
 _lib = None
 
 
@@ -114,8 +114,10 @@ def load_library():
     lib.awp_plan_destroy.argtypes = [P]
     lib.adt_ablation.restype = I
     lib.adt_ablation.argtypes = [I, I, P, P, P, I, P, P]
+    lib.adt_launch_shape.restype = I
+    lib.adt_launch_shape.argtypes = [I, I, I]
     lib.adt_stream_cache_limit.restype = I64
-    lib.adt_stream_cache_limit.argtypes = [I64]
+    lib.adt_stream_cache_limit.argtypes = [I, I64]
     lib.adt_shutdown.restype = I
     lib.adt_shutdown.argtypes = []
     _lib = lib
@@ -324,10 +326,24 @@ def adt_timing_enable(on: bool, reserve_launches: int = 0) -> None:
     _check(load_library().adt_timing_enable(1 if on else 0, int(reserve_launches)))
 
 
-def adt_stream_cache_limit(nbytes: int = -1) -> int:
-    """adt_stream_cache_limit: set (nbytes >= 0) or read the size limit below which the
-    packed stream is written with cache-friendly stores; returns the previous value."""
-    return int(load_library().adt_stream_cache_limit(int(nbytes)))
+def adt_launch_shape(kernel: str, waves: int, extra_lds_bytes: int = 0) -> None:
+    """adt_launch_shape: waves per block and unused dynamic LDS of "pack_kernel",
+    "pack_unpack_kernel" or "fused_kernel"; waves = 0 returns to the default."""
+    _check(load_library().adt_launch_shape(_kernel_index(kernel), int(waves), int(extra_lds_bytes)))
+
+
+def _kernel_index(kernel: str) -> int:
+    lib = load_library()
+    return [lib.adt_kernel_name(k).decode() for k in range(ADT_NKERNELS)].index(kernel)
+
+
+def adt_stream_cache_limit(kernel: str, nbytes: int = -1) -> int:
+    """adt_stream_cache_limit: set (nbytes >= 0) or read the size limit below which
+    "pack_kernel", or "pack_unpack_kernel" / "fused_kernel", write the packed stream with
+    cache-friendly stores; returns the previous value."""
+    n = int(load_library().adt_stream_cache_limit(_kernel_index(kernel), int(nbytes)))
+    _check(n)
+    return n
 
 
 def adt_timing_read() -> dict:

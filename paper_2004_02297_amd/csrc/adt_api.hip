@@ -21,18 +21,19 @@
 #include "adt_tile_ops.h"
 
 namespace adt {
-hipError_t launch_pack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
-                       hipStream_t stream);
+hipError_t launch_pack(const PackArgs &a, uint32_t n_tiles, bool inline_table, int waves,
+                       uint32_t extra_lds, hipStream_t stream);
 hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table, int out_format,
-                         hipStream_t stream);
+                         uint32_t extra_lds, hipStream_t stream);
 hipError_t launch_stats(const StatsArgs &a, const StatsFinalArgs &f, uint32_t n_tiles,
                         bool inline_table, hipStream_t stream);
-hipError_t launch_stats_final(const StatsFinalArgs &f, bool inline_table, hipStream_t stream);
-hipError_t launch_fused(const FusedArgs &a, int out_format, hipStream_t stream);
-hipError_t launch_redo(const FusedArgs &a, int out_format, hipStream_t stream);
-hipError_t launch_rule(const RuleArgs &a, hipStream_t stream);
+hipError_t launch_fused(const FusedArgs &a, int out_format, int waves, uint32_t extra_lds,
+                        hipStream_t stream);
+hipError_t launch_final_rule(const FinalRuleArgs &a, hipStream_t stream);
+hipError_t launch_redo(const FusedArgs &a, int out_format, int64_t *pack_off, int64_t *packed_size,
+                       int32_t *steps_done, hipStream_t stream);
 hipError_t launch_pack_unpack(const PackUnpackArgs &a, uint32_t n_tiles, bool inline_table,
-                              hipStream_t stream);
+                              int waves, uint32_t extra_lds, hipStream_t stream);
 hipError_t launch_ablation(int which, const AblationArgs &a, uint32_t n_tiles, hipStream_t s);
 }  // namespace adt
 
@@ -47,6 +48,9 @@ struct awp_plan {
     double T = 0.0;
     int interval = 0, n_bits = 0;
     int64_t steps = 0;
+    // Stream bytes per weight as last seen by the host (at creation, set_state
+    // and read); only picks the fused kernel's occupancy cap.
+    double bytes_per_weight_hint = 1.0;
     hipStream_t last_stream = nullptr;
     std::vector<int64_t> layer_sizes;   // host copy, for rebuilding the stream offsets
     std::vector<int32_t> groups;        // host copy of group_off
@@ -56,6 +60,13 @@ struct awp_plan {
     uint8_t *rbytes = nullptr;
     int32_t *bits = nullptr, *counter = nullptr, *changed = nullptr, *steps_done = nullptr;
     double *l2_prev = nullptr, *stats = nullptr, *partial_sumsq = nullptr;
+    // final + rule kernel: its sub-blocks (see adt::FinalSub)
+    int n_subs = 0;
+    std::vector<adt::FinalSub> host_subs;   // copy for the kernel arguments of small plans
+    adt::FinalSub *subs = nullptr;
+    uint32_t *layer_sub_off = nullptr, *sub_absmax = nullptr;
+    int32_t *group_subs = nullptr, *group_ticket = nullptr;
+    double *sub_sumsq = nullptr;
 };
 
 static_assert(ADT_NKERNELS == adt::kNumKernels, "adt.h and adt_launch.h disagree");
@@ -111,8 +122,20 @@ struct DeviceState {
 std::mutex g_mu;
 std::map<int, DeviceState> g_state;
 
-// Streams above this size are written with nontemporal stores (adt_tile_ops.h).
-std::atomic<int64_t> g_stream_cache_limit{adt::kStreamKeepInCacheBytes};
+// Launch shape overrides (adt_launch_shape); waves == 0: the library's own choice.
+using adt::LaunchShape;
+std::mutex g_shape_mu;
+LaunchShape g_shape[ADT_NKERNELS] = {};
+
+LaunchShape shape_of(int kernel, LaunchShape dflt) {
+    std::lock_guard<std::mutex> lock(g_shape_mu);
+    return g_shape[kernel].waves ? g_shape[kernel] : dflt;
+}
+
+// Streams above this size are written with nontemporal stores (adt_tile_ops.h):
+// one limit for adt_pack, one for the kernels that also write the truncated weights.
+std::atomic<int64_t> g_pack_cache_limit{adt::kPackStreamKeepInCacheBytes};
+std::atomic<int64_t> g_fused_cache_limit{adt::kFusedStreamKeepInCacheBytes};
 
 // ---- launch timing ----------------------------------------------------------
 struct TimedLaunch {
@@ -256,6 +279,7 @@ int check_groups(const int32_t *group_offsets, int n_groups, int n_layers,
 
 enum Direction { kPack, kUnpack, kPackUnpack, kUnpackBf16, kUnpackFp16 };
 
+
 int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
                    const uint8_t *rb, int n_layers, const void *packed, adt_stream_t stream,
                    void *weights_out = nullptr) {
@@ -280,7 +304,7 @@ int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
     a.weights = (const uint32_t *)weights;
     a.packed = (uint8_t *)packed;
     a.n_layers = n_layers;
-    a.stream_cache_limit = g_stream_cache_limit.load();
+    a.stream_cache_limit = dir == kPack ? g_pack_cache_limit.load() : g_fused_cache_limit.load();
     a.dev = adt::DeviceTable{nullptr, nullptr, nullptr, nullptr};
     const bool inl = n_layers <= adt::kInlineLayers;
     hipStream_t hs = (hipStream_t)stream;
@@ -327,7 +351,13 @@ int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
     pack_off[n_layers] = p;
     a.packed_size = p;
     const bool unpack_dir = dir == kUnpack || dir == kUnpackBf16 || dir == kUnpackFp16;
-    rc = build_tile_off(off, n_layers, unpack_dir ? adt::kUnpackBlockTile : adt::kBlockTile,
+    const double bpw = (double)p / (double)n;            // stream bytes per weight
+    const LaunchShape shape =
+        dir == kPack ? shape_of(adt::kKernelPack, adt::pack_shape(bpw))
+        : dir == kPackUnpack ? shape_of(adt::kKernelPackUnpack, adt::pack_unpack_shape(bpw))
+                             : shape_of(adt::kKernelUnpack, adt::unpack_shape(bpw));
+    rc = build_tile_off(off, n_layers,
+                        unpack_dir ? adt::kUnpackBlockTile : (int64_t)shape.waves * adt::kWaveTile,
                         tile_off);
     if (rc) return rc;
     const uint32_t n_tiles = tile_off[n_layers];
@@ -336,11 +366,14 @@ int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
         hipError_t e = hipMemcpyAsync(slot->dev, slot->host, bytes, hipMemcpyHostToDevice, hs);
         if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(table)");
     }
-    hipError_t e = dir == kPack     ? adt::launch_pack(a, n_tiles, inl, hs)
-                   : dir == kUnpack ? adt::launch_unpack(a, n_tiles, inl, 0, hs)
-                   : dir == kUnpackBf16 ? adt::launch_unpack(a, n_tiles, inl, ADT_OUT_BF16, hs)
-                   : dir == kUnpackFp16 ? adt::launch_unpack(a, n_tiles, inl, ADT_OUT_FP16, hs)
-                                        : adt::launch_pack_unpack(pu, n_tiles, inl, hs);
+    hipError_t e = dir == kPack     ? adt::launch_pack(a, n_tiles, inl, shape.waves, shape.extra_lds, hs)
+                   : dir == kUnpack ? adt::launch_unpack(a, n_tiles, inl, 0, shape.extra_lds, hs)
+                   : dir == kUnpackBf16
+                       ? adt::launch_unpack(a, n_tiles, inl, ADT_OUT_BF16, shape.extra_lds, hs)
+                   : dir == kUnpackFp16
+                       ? adt::launch_unpack(a, n_tiles, inl, ADT_OUT_FP16, shape.extra_lds, hs)
+                                        : adt::launch_pack_unpack(pu, n_tiles, inl, shape.waves,
+                                                                  shape.extra_lds, hs);
     if (!inl) {
         // guard the slot even if the launch failed: the copy may be in flight
         if (hipEventRecord(slot->ev, hs) == hipSuccess) slot->pending = true;
@@ -611,6 +644,7 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     std::vector<uint32_t> tile_off(L1);
     rc = build_tile_off(layer_offsets, n_layers, adt::kBlockTile, tile_off.data());
     if (rc) return rc;
+    if (tile_off[L] >= (1u << 29)) return fail(ADT_ERANGE, "too many tiles for one launch");
     std::vector<int32_t> bits(G);
     std::vector<uint8_t> rb(L);
     std::vector<int64_t> pack_off(L1);
@@ -637,19 +671,52 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     pl->layer_sizes.resize(L);
     for (size_t l = 0; l < L; ++l) pl->layer_sizes[l] = layer_offsets[l + 1] - layer_offsets[l];
     pl->n = layer_offsets[n_layers];
+    pl->bytes_per_weight_hint = pl->n > 0 ? (double)p / (double)pl->n : 1.0;
     pl->n_tiles = tile_off[L];
     pl->T = T;
     pl->interval = interval;
     pl->n_bits = n_bits;
 
+    // sub-blocks of the final + rule kernel: first every layer's chunks in layer
+    // order, then one empty sub-block for every group that has no layer
+    std::vector<adt::FinalSub> subs;
+    std::vector<uint32_t> layer_sub_off(L1);
+    std::vector<int32_t> group_subs(G, 0);
+    for (size_t g = 0; g < G; ++g) {
+        for (int32_t l = groups[g]; l < groups[g + 1]; ++l) {
+            layer_sub_off[(size_t)l] = (uint32_t)subs.size();
+            const uint32_t end = tile_off[(size_t)l + 1] * adt::kWavesPerBlock;
+            uint32_t at = tile_off[(size_t)l] * adt::kWavesPerBlock;
+            do {
+                const uint32_t stop = end - at > adt::kFinalChunk ? at + adt::kFinalChunk : end;
+                subs.push_back(adt::FinalSub{(int32_t)g, l, at, stop});
+                ++group_subs[g];
+                at = stop;
+            } while (at < end);
+        }
+    }
+    layer_sub_off[L] = (uint32_t)subs.size();
+    for (size_t g = 0; g < G; ++g) {
+        if (group_subs[g] == 0) {
+            subs.push_back(adt::FinalSub{(int32_t)g, -1, 0u, 0u});
+            group_subs[g] = 1;
+        }
+    }
+    const size_t S = subs.size();
+    pl->n_subs = (int)S;
+    if (S <= (size_t)adt::kFinalInlineSubs) pl->host_subs = subs;
+
     // carve one allocation; 8-byte items first
     size_t o = 0;
     auto take = [&o](size_t bytes) { size_t at = o; o += align8(bytes); return at; };
     const size_t o_elem = take(8 * L1), o_pack = take(8 * L1), o_psize = take(8);
-    const size_t o_prev = take(8 * G), o_stats = take(24 * L), o_psum = take(8 * (size_t)pl->n_tiles);
-    const size_t o_tile = take(4 * L1), o_pmax = take(4 * (size_t)pl->n_tiles);
+    const size_t n_partials = (size_t)pl->n_tiles * adt::kWavesPerBlock;   // one per wave tile
+    const size_t o_prev = take(8 * G), o_stats = take(24 * L), o_psum = take(8 * n_partials);
+    const size_t o_tile = take(4 * L1), o_pmax = take(4 * n_partials);
     const size_t o_bits = take(4 * G), o_cnt = take(4 * G), o_grp = take(4 * (G + 1));
     const size_t o_chg = take(4), o_steps = take(4), o_rb = take(L);
+    const size_t o_subs = take(sizeof(adt::FinalSub) * S), o_ssum = take(8 * S), o_smax = take(4 * S);
+    const size_t o_lso = take(4 * L1), o_gsubs = take(4 * G), o_gtick = take(4 * G);
     const size_t total = o + 8;
     e = hipMalloc((void **)&pl->block, total);
     if (e != hipSuccess) { (void)hipGetLastError(); delete pl; return fail(ADT_ENOMEM, "plan tables"); }
@@ -668,6 +735,12 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     pl->changed = (int32_t *)(b + o_chg);
     pl->steps_done = (int32_t *)(b + o_steps);
     pl->rbytes = (uint8_t *)(b + o_rb);
+    pl->subs = (adt::FinalSub *)(b + o_subs);
+    pl->sub_sumsq = (double *)(b + o_ssum);
+    pl->sub_absmax = (uint32_t *)(b + o_smax);
+    pl->layer_sub_off = (uint32_t *)(b + o_lso);
+    pl->group_subs = (int32_t *)(b + o_gsubs);
+    pl->group_ticket = (int32_t *)(b + o_gtick);
 
     e = hipMemset(b, 0, total);
     if (e == hipSuccess) e = hipMemcpy(pl->elem_off, layer_offsets, 8 * L1, hipMemcpyHostToDevice);
@@ -678,6 +751,12 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     if (e == hipSuccess)
         e = hipMemcpy(pl->group_off, groups.data(), 4 * (G + 1), hipMemcpyHostToDevice);
     if (e == hipSuccess && L) e = hipMemcpy(pl->rbytes, rb.data(), L, hipMemcpyHostToDevice);
+    if (e == hipSuccess && S)
+        e = hipMemcpy(pl->subs, subs.data(), sizeof(adt::FinalSub) * S, hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = hipMemcpy(pl->layer_sub_off, layer_sub_off.data(), 4 * L1, hipMemcpyHostToDevice);
+    if (e == hipSuccess && G)
+        e = hipMemcpy(pl->group_subs, group_subs.data(), 4 * G, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         (void)hipFree(pl->block);
@@ -739,47 +818,45 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
     a.partial_sumsq = plan->partial_sumsq;
     a.partial_absmax = plan->partial_absmax;
     a.changed = plan->changed;
-    a.stream_cache_limit = g_stream_cache_limit.load();
+    a.stream_cache_limit = g_fused_cache_limit.load();
     a.n_layers = plan->n_layers;
     a.n_tiles = plan->n_tiles;
 
     if (plan->n_tiles > 0) {
-        e = adt::launch_fused(a, out_format, hs);
+        const LaunchShape shape =
+            shape_of(adt::kKernelFused, adt::fused_shape(plan->bytes_per_weight_hint));
+        e = adt::launch_fused(a, out_format, shape.waves, shape.extra_lds, hs);
         if (e != hipSuccess) return fail_hip(e, "fused launch");
     }
-    adt::StatsFinalArgs f;
-    f.partial_sumsq = plan->partial_sumsq;
-    f.partial_absmax = plan->partial_absmax;
-    f.stats_out = plan->stats;
-    f.n_layers = plan->n_layers;
-    f.dev_tile_off = plan->tile_off;
-    e = adt::launch_stats_final(f, false, hs);
-    if (e != hipSuccess) return fail_hip(e, "statistics final launch");
-
-    adt::RuleArgs r;
+    adt::FinalRuleArgs r;
+    r.partial_sumsq = plan->partial_sumsq;
+    r.partial_absmax = plan->partial_absmax;
+    r.subs = plan->subs;
+    r.layer_sub_off = plan->layer_sub_off;
+    r.group_subs = plan->group_subs;
+    r.group_ticket = plan->group_ticket;
+    r.sub_sumsq = plan->sub_sumsq;
+    r.sub_absmax = plan->sub_absmax;
     r.stats = plan->stats;
     r.group_off = plan->group_off;
-    r.n_groups = plan->n_groups;
+    r.n_subs = plan->n_subs;
+    for (size_t i = 0; i < plan->host_subs.size(); ++i) r.inl_subs[i] = plan->host_subs[i];
     r.l2_prev = plan->l2_prev;
     r.bits = plan->bits;
     r.counter = plan->counter;
     r.rbytes = plan->rbytes;
-    r.elem_off = plan->elem_off;
-    r.pack_off = plan->pack_off;
     r.changed = plan->changed;
-    r.packed_size = plan->packed_size;
-    r.n_layers = plan->n_layers;
+    r.steps_done = plan->steps_done;
     r.T = plan->T;
     r.interval = plan->interval;
     r.n_bits = plan->n_bits;
-    r.steps_done = plan->steps_done;
-    e = adt::launch_rule(r, hs);
-    if (e != hipSuccess) return fail_hip(e, "rule launch");
-    ++plan->steps;
-    if (plan->n_tiles > 0) {
-        e = adt::launch_redo(a, out_format, hs);
-        if (e != hipSuccess) return fail_hip(e, "redo launch");
+    if (plan->n_subs > 0) {
+        e = adt::launch_final_rule(r, hs);
+        if (e != hipSuccess) return fail_hip(e, "final + rule launch");
     }
+    ++plan->steps;
+    e = adt::launch_redo(a, out_format, plan->pack_off, plan->packed_size, plan->steps_done, hs);
+    if (e != hipSuccess) return fail_hip(e, "redo launch");
     return ADT_OK;
 }
 }  // namespace
@@ -798,9 +875,12 @@ int awp_plan_read(awp_plan *plan, double *stats, int32_t *bits, int32_t *counter
     get(bits, plan->bits, 4 * (size_t)plan->n_groups);
     get(counter, plan->counter, 4 * (size_t)plan->n_groups);
     get(bytes, plan->rbytes, L);
-    get(packed_size, plan->packed_size, 8);
+    int64_t size_now = 0;
+    get(&size_now, plan->packed_size, 8);
     if (e == hipSuccess) e = hipStreamSynchronize(hs);
     if (e != hipSuccess) return fail_hip(e, "plan read");
+    if (packed_size) *packed_size = size_now;
+    if (plan->n > 0) plan->bytes_per_weight_hint = (double)size_now / (double)plan->n;
     return ADT_OK;
 }
 
@@ -855,6 +935,7 @@ int awp_plan_set_state(awp_plan *plan, const int32_t *bits, const int32_t *count
     put(plan->steps_done, &seen, 4);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) return fail_hip(e, "plan set_state");
+    if (plan->n > 0) plan->bytes_per_weight_hint = (double)p / (double)plan->n;
     return ADT_OK;
 }
 
@@ -969,9 +1050,28 @@ const char *adt_last_error(void) { return g_err.c_str(); }
 #endif
 const char *adt_source_digest(void) { return ADT_SOURCE_DIGEST; }
 
-int64_t adt_stream_cache_limit(int64_t bytes) {
-    if (bytes < 0) return g_stream_cache_limit.load();
-    return g_stream_cache_limit.exchange(bytes);
+int64_t adt_stream_cache_limit(int kernel, int64_t bytes) {
+    std::atomic<int64_t> *limit = kernel == adt::kKernelPack ? &g_pack_cache_limit
+                                  : kernel == adt::kKernelPackUnpack || kernel == adt::kKernelFused
+                                      ? &g_fused_cache_limit
+                                      : nullptr;
+    if (!limit) return fail(ADT_EINVAL, "stream cache limit: kernel must be pack, pack_unpack or fused");
+    if (bytes < 0) return limit->load();
+    return limit->exchange(bytes);
+}
+
+int adt_launch_shape(int kernel, int waves, int extra_lds_bytes) {
+    const bool ok_kernel = kernel == adt::kKernelPack || kernel == adt::kKernelPackUnpack ||
+                           kernel == adt::kKernelFused || kernel == adt::kKernelUnpack;
+    if (!ok_kernel)
+        return fail(ADT_EINVAL, "launch shape: kernel must be pack, unpack, pack_unpack or fused");
+    const bool ok_waves = waves == 0 || waves == 1 || (waves == 4 && kernel != adt::kKernelUnpack);
+    if (!ok_waves) return fail(ADT_EINVAL, "launch shape: waves must be 0, 1 or 4 (unpack: 0 or 1)");
+    if (extra_lds_bytes < 0 || extra_lds_bytes > 48 * 1024)
+        return fail(ADT_EINVAL, "launch shape: extra LDS must be within 0..48 KiB");
+    std::lock_guard<std::mutex> lock(g_shape_mu);
+    g_shape[kernel] = LaunchShape{waves, (uint32_t)extra_lds_bytes};
+    return ADT_OK;
 }
 
 int adt_timing_enable(int on, int reserve_launches) {
@@ -1018,10 +1118,11 @@ const char *adt_kernel_name(int kernel) {
         case adt::kKernelStatsPartial: return "stats_partial_kernel";
         case adt::kKernelStatsFinal: return "stats_final_kernel";
         case adt::kKernelFused: return "fused_kernel";
-        case adt::kKernelRule: return "rule_kernel";
+        case adt::kKernelFinalRule: return "final_rule_kernel";
         case adt::kKernelRedo: return "redo_kernel";
         case adt::kKernelPackUnpack: return "pack_unpack_kernel";
         case adt::kKernelUnpack16: return "unpack16_kernel";
+        case adt::kKernelPrefix: return "prefix_kernel";
         default: return "";
     }
 }

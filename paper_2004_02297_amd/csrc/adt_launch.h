@@ -18,11 +18,12 @@ enum KernelId {
     kKernelStatsPartial = 2,
     kKernelStatsFinal = 3,
     kKernelFused = 4,
-    kKernelRule = 5,
+    kKernelFinalRule = 5,
     kKernelRedo = 6,
     kKernelPackUnpack = 7,
     kKernelUnpack16 = 8,
-    kNumKernels = 9
+    kKernelPrefix = 9,
+    kNumKernels = 10
 };
 
 // Defined in adt_api.hip.  True (and a fresh event pair, owned by the timing

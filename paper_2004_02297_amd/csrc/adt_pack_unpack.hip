@@ -31,12 +31,12 @@ namespace adt {
 // ---------------------------------------------------------------------------
 // Kernels: block -> (layer, tile) through the offset table, wave -> wave tile.
 // ---------------------------------------------------------------------------
-template <bool INLINE>
-__global__ __launch_bounds__(kBlock) void pack_kernel(const PackArgs a) {
-    __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
+template <bool INLINE, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void pack_kernel(const PackArgs a) {
+    __shared__ __attribute__((aligned(16))) uint32_t smem[WAVES][kWaveLdsDw];
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
-    const TileRef t = locate<INLINE>(a, blockIdx.x, wave);
+    const TileRef t = locate<INLINE, WAVES>(a, blockIdx.x, wave);
     if (t.len == 0) return;
     const uint32_t *src = a.weights + t.elem;
     uint8_t *dst = a.packed + t.byte;
@@ -73,14 +73,17 @@ __global__ __launch_bounds__(kUnpackWaves * kWave) void unpack_kernel(const Pack
     }
 }
 
-hipError_t launch_pack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
-                       hipStream_t stream) {
-    return inline_table ? launch(pack_kernel<true>, kKernelPack, n_tiles, kBlock, stream, a)
-                        : launch(pack_kernel<false>, kKernelPack, n_tiles, kBlock, stream, a);
+// waves: 1 or 4 (the tile table must have been built for waves * 1024 weights per block)
+hipError_t launch_pack(const PackArgs &a, uint32_t n_tiles, bool inline_table, int waves,
+                       uint32_t extra_lds, hipStream_t stream) {
+    void (*k)(PackArgs);
+    if (waves == 1) k = inline_table ? pack_kernel<true, 1> : pack_kernel<false, 1>;
+    else k = inline_table ? pack_kernel<true, 4> : pack_kernel<false, 4>;
+    return launch(k, kKernelPack, n_tiles, waves * kWave, stream, a, extra_lds);
 }
 
 hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table, int out_format,
-                         hipStream_t stream) {
+                         uint32_t extra_lds, hipStream_t stream) {
     void (*k)(PackArgs);
     if (inline_table)
         k = out_format == kOutFp32   ? unpack_kernel<true, kOutFp32>
@@ -91,7 +94,7 @@ hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table,
             : out_format == kOutBf16 ? unpack_kernel<false, kOutBf16>
                                      : unpack_kernel<false, kOutFp16>;
     return launch(k, out_format == kOutFp32 ? kKernelUnpack : kKernelUnpack16, n_tiles,
-                  kUnpackWaves * kWave, stream, a, kUnpackExtraLds);
+                  kUnpackWaves * kWave, stream, a, extra_lds);
 }
 
 }  // namespace adt

@@ -20,10 +20,8 @@ constexpr int kBlock = kWave * kWavesPerBlock;
 constexpr int kChunksPerLane = ADT_CHUNKS_PER_LANE;   // 128-bit loads in flight per lane
 constexpr int kWaveTile = kWave * kChunksPerLane * 4;    // 1024 weights per wave
 constexpr int kBlockTile = kWaveTile * kWavesPerBlock;   // 4096 weights per block
-// Unpack runs one wavefront per block: its waves finish at uneven times (the
-// stores dominate), and single-wave blocks let a new tile start the moment any
-// wave slot frees up instead of when a whole four-wave block has drained
-// (138 M weights at 2 bytes: 141 us instead of 151 us).
+// Unpack always runs one wavefront per block; pack, pack + unpack and the
+// fused kernel of the plan can run one or four (see "launch shapes" below).
 constexpr int kUnpackWaves = 1;
 constexpr int kUnpackBlockTile = kWaveTile * kUnpackWaves;
 
@@ -31,20 +29,68 @@ constexpr int kUnpackBlockTile = kWaveTile * kUnpackWaves;
 constexpr int kStatsLoadsPerLane = 8;
 constexpr int kStatsTile = kBlock * kStatsLoadsPerLane * 4;
 
-// Waves in flight.  On MI355X a streaming kernel does not always sustain the
-// most bandwidth with the 32 waves per compute unit the hardware could hold: a
-// copy-like probe runs at 6.1 TB/s with 32 waves and 6.5 TB/s with 16, one read
-// per two writes at 5.8 vs 6.6 TB/s, a pure read at 6.9 vs 7.2 TB/s.  Unpack
-// (138 M weights, after pack, at 1 / 2 / 3 / 4 bytes: 119 / 117 / 156 / 173 us
-// with 19 waves, 124 / 122 / 163 / 176 us uncapped; 15 waves are as good from
-// 2 bytes up but cost 11 % at 1 byte) and the statistics kernel (76.9 vs
-// 79.0 us with 16 waves) gain; pack and the fused kernel do not, and stay
-// uncapped.  The launchers request this much dynamic LDS that no kernel
-// touches, so that a compute unit (160 KB of LDS) holds fewer blocks:
-constexpr uint32_t kUnpackExtraLds = 4096;    // 4.1 + 4 KB per 1-wave block -> 19 blocks
-constexpr uint32_t kStatsExtraLds = 36864;    // 4-wave blocks               -> 4 blocks
+// Launch shapes.  On MI355X a streaming kernel sustains the most bandwidth with
+// far fewer waves in flight than a compute unit could hold (32): measured on
+// 138 M weights with rotating output buffers (so that the last-level cache
+// cannot absorb rewrites), the kernels that write more than they read are
+// fastest with 9 to 13 waves per compute unit and lose 5 to 10 % at 32.  Two
+// things make such a low occupancy work: blocks of ONE wavefront, so that a
+// compute unit is refilled the moment any wave retires (a four-wave block holds
+// the slots of its finished waves until the last one drains), and a wave that
+// reaches its first streaming load without any vector-memory round trip (all
+// table look-ups are scalar loads, see table_load).  The launchers request
+// dynamic LDS that no kernel touches; a compute unit has 160 KB, a one-wave
+// block of the pack / unpack kernels owns 4160 B of its own:
+//   extra 4 KB -> 19 waves, 6 KB -> 15, 8 KB -> 13, 10 KB -> 11, 12 KB -> 9.
+// Microseconds per launch, 138 M weights, all layers at 1 / 2 / 3 / 4 bytes:
+//   fused (plan)   4-wave blocks, no cap   223 / 250 / 283 / 298
+//                  1-wave, 8 KB            199 / 220 / 255 / 273
+//                  1-wave, 10 KB           211 / 224 / 248 / 263
+//   pack + unpack  1-wave, 8 / 10 / 12 KB  194 / 217 / 244 / 259 (best of the three)
+//   pack           1-wave, 4 KB            110 / 127 / 151 / 171   (4-wave: 112 / 129 / 152 / 175)
+//   unpack         1-wave, 6 KB / 8 KB     111 / 129 / 155 / 170   (no cap: 129 / 145 / 166 / 180)
+// The cap is chosen from the stream's bytes per weight (how write-heavy the
+// launch is).
+struct LaunchShape {
+    int waves;            // wavefronts per block: 1 or 4
+    uint32_t extra_lds;   // bytes of dynamic LDS nothing touches
+};
+inline LaunchShape fused_shape(double bytes_per_weight) {
+    return LaunchShape{1, bytes_per_weight <= 2.5 ? 8192u : 10240u};
+}
+inline LaunchShape pack_unpack_shape(double bytes_per_weight) {
+    return LaunchShape{1, bytes_per_weight <= 1.5 ? 8192u : bytes_per_weight <= 2.6 ? 10240u : 12288u};
+}
+inline LaunchShape pack_shape(double) { return LaunchShape{1, 4096u}; }
+inline LaunchShape unpack_shape(double bytes_per_weight) {
+    return LaunchShape{kUnpackWaves, bytes_per_weight <= 1.5 ? 6144u : 8192u};
+}
+// Statistics: 4-wave blocks, 16 waves per compute unit (76.9 us instead of 79.0 us uncapped).
+constexpr uint32_t kStatsExtraLds = 36864;
 
 constexpr int kInlineLayers = 128;
+
+#if defined(__HIPCC__)
+// Wave-uniform read of a table entry that nothing writes while the kernel runs.
+// The read goes through the constant address space: that tells the compiler the
+// data is invariant, so it issues a scalar load.  Through an ordinary global
+// pointer it would issue a vector memory load, and a block's binary search over
+// the table would become a chain of round trips through the (saturated) vector
+// memory pipeline before the wave can issue its first streaming load.
+template <typename T>
+__device__ __forceinline__ T table_load(const T *table, int64_t idx) {
+    typedef const T __attribute__((address_space(4))) *ConstantPtr;
+    return ((ConstantPtr)table)[idx];
+}
+
+// Entry idx of a byte table through a scalar dword load (there is no scalar
+// byte load).  The table must be 4-byte aligned and readable up to the next
+// multiple of four entries; idx must be wave uniform.
+__device__ __forceinline__ int table_byte(const uint8_t *table, int idx) {
+    const uint32_t word = table_load((const uint32_t *)table, idx >> 2);
+    return (int)((word >> (8 * (idx & 3))) & 0xFFu);
+}
+#endif
 
 // Layer l covers weights [elem_off[l], elem_off[l+1]), packed bytes
 // [pack_off[l], pack_off[l+1]) and tiles [tile_off[l], tile_off[l+1]).
@@ -125,31 +171,52 @@ struct FusedArgs {
     const int64_t *pack_off;
     const uint32_t *tile_off;
     const uint8_t *rbytes;
-    double *partial_sumsq;      // one per block tile
+    double *partial_sumsq;      // one per wave tile: 4 * n_tiles entries
     uint32_t *partial_absmax;
-    const int32_t *changed;
+    int32_t *changed;           // cleared by the fused kernel, raised by the rule, read by redo
     int64_t stream_cache_limit;   // streams larger than this are written nontemporal
     int n_layers;
     uint32_t n_tiles;
 };
 
-struct RuleArgs {
-    const double *stats;        // n_layers x 3, written by the final kernel
+// Final reduction of the statistics + Algorithm 1.  The partials of a layer
+// are cut into chunks of kFinalChunk; one block ("sub-block") reduces one chunk.
+// Every layer has at least one sub-block (an empty layer: an empty chunk) and
+// every group at least one (a group without layers: one that reduces nothing),
+// so that each group's rule runs.
+constexpr uint32_t kFinalChunk = 8192;
+struct FinalSub {           // work of one sub-block
+    int32_t group;
+    int32_t layer;          // -1: the group has no layer
+    uint32_t begin, end;    // partials [begin, end) of that layer
+};
+constexpr int kFinalInlineSubs = 96;   // up to this many sub-blocks ride in the kernel arguments
+struct FinalRuleArgs {
+    const double *partial_sumsq;
+    const uint32_t *partial_absmax;
+    const FinalSub *subs;           // one per block of the launch (used beyond kFinalInlineSubs)
+    const uint32_t *layer_sub_off;  // n_layers + 1: sub-blocks of layer l are [off[l], off[l+1])
+    const int32_t *group_subs;      // per group: number of its sub-blocks
+    int32_t *group_ticket;          // per group: sub-blocks finished in this launch (0 between launches)
+    double *sub_sumsq;              // one per sub-block
+    uint32_t *sub_absmax;
+    double *stats;              // n_layers x 3
     const int32_t *group_off;   // n_groups + 1 layer indices
-    int n_groups;
+    int n_subs;                 // blocks of the launch
     double *l2_prev;            // per group
     int32_t *bits;              // per group
     int32_t *counter;           // per group
-    uint8_t *rbytes;
-    const int64_t *elem_off;
-    int64_t *pack_off;
+    uint8_t *rbytes;            // per layer
     int32_t *changed;
-    int64_t *packed_size;
-    int n_layers;
+    const int32_t *steps_done;  // 0 before the first batch: that batch only records norms
     double T;
     int interval;
     int n_bits;
-    int32_t *steps_done;        // 0 before the first batch: that batch only records norms
+    FinalSub inl_subs[kFinalInlineSubs];
 };
+
+// Redo pass: layers whose stream-offset table fits the kernel's LDS, and its grid.
+constexpr int kRedoLdsLayers = 4096;
+constexpr int kRedoBlocks = 256;
 
 }  // namespace adt

@@ -20,14 +20,21 @@ typedef u32x4 u32x4_a4 __attribute__((aligned(4)));   // FP32 side: dword aligne
 // and the stream is read once by unpack: those accesses carry the nontemporal
 // hint, so their lines are not kept in L2 / Infinity Cache (on MI355X this
 // raises the sustained read rate by about 10 %).  How the stream is WRITTEN
-// depends on its size: a stream that about fits the 256 MB Infinity Cache is
-// written with ordinary stores, so that the consumer right behind it (unpack,
-// or a copy engine sending it to a peer) finds it there and its write-back
-// overlaps later work; a larger one would only thrash the cache and is written
-// nontemporal as well.  Measured on 138 M weights, whole pass through the
-// plan: 2-byte stream (264 MiB) 210 us cacheable vs 231 us nontemporal; mixed
-// stream of 295 MiB 247 vs 244 us; 3-byte stream (396 MiB) 273 vs 263 us.
-constexpr int64_t kStreamKeepInCacheBytes = (int64_t)280 << 20;   // default of the limit
+// depends on who reads it next.  Measured on 138 M weights with rotating output
+// buffers (so that a rewrite of the same buffer cannot be absorbed by the
+// 256 MB Infinity Cache):
+//  - adt_pack with adt_unpack right behind it: ordinary stream stores let
+//    unpack find much of the stream in the cache.  pack + unpack at 2 bytes
+//    (264 MiB stream) 238 us vs 257 us with nontemporal stores, mixed bytes
+//    (295 MiB) 249 vs 269 us, 3 bytes (396 MiB) 313 vs 309 us: ordinary stores
+//    up to 320 MiB, nontemporal above.
+//  - the kernels that also write the truncated weights (adt_pack_unpack, the
+//    plan's fused kernel): nothing on the device reads the stream right behind
+//    them (a device-to-device copy of the stream placed there runs equally fast
+//    either way), and nontemporal stores are 2 - 5 % faster at every size
+//    (2 bytes: 218 vs 224 us, 4 bytes: 261 vs 274 us): always nontemporal.
+constexpr int64_t kPackStreamKeepInCacheBytes = (int64_t)320 << 20;
+constexpr int64_t kFusedStreamKeepInCacheBytes = 0;
 
 #ifndef ADT_NT_FP32_LOAD
 #define ADT_NT_FP32_LOAD 1
@@ -372,16 +379,16 @@ __device__ __forceinline__ TileRef locate(const PackArgs &a, uint32_t block, int
     int lo = 0, hi = a.n_layers;            // largest lo with tile_off[lo] <= block
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
-        if (tile_off[mid] <= block) lo = mid; else hi = mid;
+        if (table_load(tile_off, mid) <= block) lo = mid; else hi = mid;
     }
-    const int64_t e_begin = elem_off[lo];
-    const int64_t n = elem_off[lo + 1] - e_begin;
-    const int64_t first = (int64_t)(block - tile_off[lo]) * (WAVES * kWaveTile) +
+    const int64_t e_begin = table_load(elem_off, lo);
+    const int64_t n = table_load(elem_off, lo + 1) - e_begin;
+    const int64_t first = (int64_t)(block - table_load(tile_off, lo)) * (WAVES * kWaveTile) +
                           (int64_t)wave * kWaveTile;
     TileRef t;
-    t.r = rbytes[lo];
+    t.r = table_byte(rbytes, lo);
     t.elem = e_begin + first;
-    t.byte = pack_off[lo] + first * t.r;
+    t.byte = table_load(pack_off, lo) + first * t.r;
     const int64_t left = n - first;
     t.len = left <= 0 ? 0 : (left < kWaveTile ? (int)left : kWaveTile);
     return t;

@@ -6,18 +6,20 @@
 // The byte count of a layer changes at most a handful of times in a whole
 // training run (Algorithm 1 adds N bits after INTERVAL counted batches), so the
 // pass speculates that this batch keeps the previous batch's byte counts:
-//   1. fused kernel   : every wave tile of 1024 weights is loaded once; its
-//                       sum of squares and largest magnitude go to a per-block
-//                       partial, its top r bytes go to the packed stream and the
-//                       truncated words (what Bitunpack would return) go to the
-//                       output weights.
-//   2. final kernel   : per-layer reduction of the partials (fixed order).
-//   3. rule kernel    : one block runs Algorithm 1 on the fresh norms, rewrites
-//                       the byte counts and the stream offsets (prefix sum) and
-//                       raises `changed` if any byte count moved.
-//   4. redo kernel    : a small persistent grid that returns at once unless
-//                       `changed` is set; then it packs and truncates again with
-//                       the new table.
+//   1. fused kernel      : every wave tile of 1024 weights is loaded once; its
+//                          sum of squares and largest magnitude go to a partial
+//                          of its own, its top r bytes go to the packed stream
+//                          and the truncated words (what Bitunpack would
+//                          return) go to the output weights.
+//   2. final+rule kernel : the partials of every layer are reduced in a fixed
+//                          order (big layers by several blocks), then Algorithm
+//                          1 runs per layer group: new bit count, interval
+//                          counter, byte counts of the group's layers, and the
+//                          flag `changed` if a byte count moved.
+//   3. redo kernel       : a small grid that returns at once unless `changed`
+//                          is set; then every block rebuilds the stream offsets
+//                          (prefix sum of n_l * r_l) and the grid packs and
+//                          truncates again with the new byte counts.
 // The result is what statistics -> rule -> pack -> unpack would give in that
 // order, whether or not the speculation held.
 #include <hip/hip_runtime.h>
@@ -26,30 +28,9 @@
 #include "adt_launch.h"
 #include "adt_tables.h"
 #include "adt_tile_ops.h"
+#include "awp_partials.h"
 
 namespace adt {
-
-__device__ __forceinline__ double fused_wave_sum(double v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
-}
-
-__device__ __forceinline__ uint32_t fused_wave_max(uint32_t v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const uint32_t o = (uint32_t)__shfl_xor((int)v, off, kWave);
-        v = o > v ? o : v;
-    }
-    return v;
-}
-
-__device__ __forceinline__ void square_add(uint32_t bits, double &acc, uint32_t &mag) {
-    const double w = (double)__uint_as_float(bits);
-    acc = fma(w, w, acc);               // the square of a binary32 is exact in binary64
-    const uint32_t m = bits & 0x7FFFFFFFu;
-    mag = m > mag ? m : mag;            // NaN patterns order above infinity
-}
 
 // Truncated words of a loaded wave tile -> output weights (what unpack, or
 // unpack to a 16-bit format, returns).  dst: the tile's first output element.
@@ -66,6 +47,9 @@ __device__ __forceinline__ void store_truncated(const u32x4 (&v)[kChunksPerLane]
     }
 }
 
+// One wave tile: load once, then statistics (this lane's share of the tile's
+// sum of squares in `sum`, largest magnitude folded into `mag`), truncated
+// words and stream bytes.
 template <int R, bool STATS, int OUT>
 __device__ __forceinline__ void fused_wave_tile(const uint32_t *__restrict__ src,
                                                 uint8_t *__restrict__ stream,
@@ -89,87 +73,265 @@ __device__ __forceinline__ void fused_wave_tile(const uint32_t *__restrict__ src
     stream_out_wave_tile<R>(v, stream, len, lds, lane, stream_nt);
 }
 
-template <bool STATS, int OUT>
-__device__ __forceinline__ void fused_block_tile(const FusedArgs &a, uint32_t tile, int wave,
-                                                 int lane, uint32_t *lds, double &sum,
-                                                 uint32_t &mag) {
+// The layer a block tile belongs to, and where the tile starts in it.
+struct BlockTileRef {
+    int layer;
+    int r;               // byte count of the layer
+    int64_t elem;        // absolute index of the tile's first weight
+    int64_t in_layer;    // index of that weight inside its layer
+    int64_t layer_size;
+};
+
+__device__ __forceinline__ BlockTileRef find_block_tile(const FusedArgs &a, uint32_t tile) {
     int lo = 0, hi = a.n_layers;            // largest lo with tile_off[lo] <= tile
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
-        if (a.tile_off[mid] <= tile) lo = mid; else hi = mid;
+        if (table_load(a.tile_off, mid) <= tile) lo = mid; else hi = mid;
     }
-    const int64_t e_begin = a.elem_off[lo];
-    const int64_t first = (int64_t)(tile - a.tile_off[lo]) * kBlockTile + (int64_t)wave * kWaveTile;
-    const int64_t left = (a.elem_off[lo + 1] - e_begin) - first;
+    BlockTileRef t;
+    t.layer = lo;
+    const int64_t e_begin = table_load(a.elem_off, lo);
+    t.layer_size = table_load(a.elem_off, lo + 1) - e_begin;
+    t.in_layer = (int64_t)(tile - table_load(a.tile_off, lo)) * kBlockTile;
+    t.elem = e_begin + t.in_layer;
+    t.r = table_byte(a.rbytes, lo);
+    return t;
+}
+
+// Wave tile k (0..3) of a block tile.  layer_stream: where the layer's stream
+// starts (from the table in global memory in the speculative pass, from the
+// table rebuilt in LDS in the redo pass).
+template <bool STATS, int OUT>
+__device__ __forceinline__ void fused_block_wave_tile(const FusedArgs &a, const BlockTileRef &t,
+                                                      int64_t layer_stream, bool stream_nt,
+                                                      int k, int lane, uint32_t *lds,
+                                                      double &sum, uint32_t &mag) {
+    const int64_t first = t.in_layer + (int64_t)k * kWaveTile;
+    const int64_t left = t.layer_size - first;
     const int len = __builtin_amdgcn_readfirstlane(
         left <= 0 ? 0 : (left < kWaveTile ? (int)left : kWaveTile));
     if (len == 0) return;
-    const int r = __builtin_amdgcn_readfirstlane((int)a.rbytes[lo]);
-    const uint32_t *src = a.weights + e_begin + first;
-    uint8_t *stream = a.packed + a.pack_off[lo] + first * r;
+    const int64_t e = t.elem + (int64_t)k * kWaveTile;
+    const uint32_t *src = a.weights + e;
+    uint8_t *stream = a.packed + layer_stream + first * t.r;
     void *wout = OUT == kOutNone ? nullptr
-                 : OUT == kOutFp32 ? (void *)((uint32_t *)a.weights_out + e_begin + first)
-                                   : (void *)((uint16_t *)a.weights_out + e_begin + first);
-    const bool nt = a.pack_off[a.n_layers] > a.stream_cache_limit;   // whole stream's size
-    switch (r) {
-        case 1: fused_wave_tile<1, STATS, OUT>(src, stream, wout, len, lds, lane, nt, sum, mag); break;
-        case 2: fused_wave_tile<2, STATS, OUT>(src, stream, wout, len, lds, lane, nt, sum, mag); break;
-        case 3: fused_wave_tile<3, STATS, OUT>(src, stream, wout, len, lds, lane, nt, sum, mag); break;
-        default: fused_wave_tile<4, STATS, OUT>(src, stream, wout, len, lds, lane, nt, sum, mag); break;
+                 : OUT == kOutFp32 ? (void *)((uint32_t *)a.weights_out + e)
+                                   : (void *)((uint16_t *)a.weights_out + e);
+    switch (t.r) {
+        case 1: fused_wave_tile<1, STATS, OUT>(src, stream, wout, len, lds, lane, stream_nt, sum, mag); break;
+        case 2: fused_wave_tile<2, STATS, OUT>(src, stream, wout, len, lds, lane, stream_nt, sum, mag); break;
+        case 3: fused_wave_tile<3, STATS, OUT>(src, stream, wout, len, lds, lane, stream_nt, sum, mag); break;
+        default: fused_wave_tile<4, STATS, OUT>(src, stream, wout, len, lds, lane, stream_nt, sum, mag); break;
     }
 }
 
-// Speculative pass: one block tile (4096 weights) per block, statistics on.
-template <int OUT>
-__global__ __launch_bounds__(kBlock) void fused_kernel(const FusedArgs a) {
-    __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
-    __shared__ double wsum[kWavesPerBlock];
-    __shared__ uint32_t wmag[kWavesPerBlock];
+// Speculative pass.  Wave tile number wt = 4 * (block tile) + k gets one
+// wavefront, which writes one statistics partial, partial[wt]; no wavefront
+// talks to another one.  The launch shape only decides how the wavefronts are
+// grouped into blocks: four per block (block = block tile) or one per block
+// (then a compute unit can be filled in steps of one wave, which is what the
+// occupancy caps of the launchers need to work well).  Results do not depend
+// on the shape.
+template <int OUT, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void fused_kernel(const FusedArgs a) {
+    __shared__ __attribute__((aligned(16))) uint32_t smem[WAVES][kWaveLdsDw];
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
+    const uint32_t wt = WAVES == 1 ? blockIdx.x : blockIdx.x * (uint32_t)kWavesPerBlock + (uint32_t)wave;
+    if (wt == 0 && lane == 0) *a.changed = 0;             // raised by the rule if need be
+    const BlockTileRef t = find_block_tile(a, wt / kWavesPerBlock);
+    const bool nt = table_load(a.pack_off, a.n_layers) > a.stream_cache_limit;   // whole stream
     double sum = 0.0;
     uint32_t mag = 0u;
-    fused_block_tile<true, OUT>(a, blockIdx.x, wave, lane, smem[wave], sum, mag);
-    sum = fused_wave_sum(sum);
-    mag = fused_wave_max(mag);
+    fused_block_wave_tile<true, OUT>(a, t, table_load(a.pack_off, t.layer), nt,
+                                     (int)(wt % kWavesPerBlock), lane, smem[wave], sum, mag);
+    sum = wave_sum(sum);       // a wave tile beyond its layer's end contributes zeros
+    mag = wave_max(mag);
     if (lane == 0) {
-        wsum[wave] = sum;
-        wmag[wave] = mag;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        a.partial_sumsq[blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
-        uint32_t m = wmag[0];
-#pragma unroll
-        for (int i = 1; i < kWavesPerBlock; ++i) m = wmag[i] > m ? wmag[i] : m;
-        a.partial_absmax[blockIdx.x] = m;
+        a.partial_sumsq[wt] = sum;
+        a.partial_absmax[wt] = mag;
     }
 }
 
-// Redo pass: persistent grid; does nothing unless the rule changed a byte count.
-template <int OUT>
-__global__ __launch_bounds__(kBlock) void redo_kernel(const FusedArgs a) {
-    __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
+// Statistics of every layer, then Algorithm 1 for every group, in one launch.
+// Phase 1: each block reduces one chunk of one layer's partials (fixed order)
+// to a sub-partial.  Phase 2: the block that finishes last among the blocks of
+// a group (a ticket counter per group; release / acquire fences around it, the
+// one place in the library where a block reads what another block of the same
+// launch wrote) adds up each of the group's layers from its sub-partials, again
+// in an order fixed by the indices alone, writes the statistics and runs the
+// rule for the group.  Which block happens to be last has no influence on any
+// result.
+template <bool INLINE>
+__global__ __launch_bounds__(kFinalBlock) void final_rule_kernel(const FinalRuleArgs a) {
+    __shared__ int is_last;
+    const FinalSub me = INLINE ? a.inl_subs[blockIdx.x] : a.subs[blockIdx.x];
+    const int g = me.group;
+    // what the rule will need, requested early so that it arrives behind the partials
+    int bits = 0, counter = 0, n_subs = 0, seen = 0;
+    double prev = 0.0;
+    if (threadIdx.x == 0) {
+        n_subs = a.group_subs[g];
+        bits = a.bits[g];
+        counter = a.counter[g];
+        prev = a.l2_prev[g];
+        seen = *a.steps_done;
+    }
+    double tot;
+    uint32_t tm;
+    reduce_partials(a.partial_sumsq, a.partial_absmax, me.begin, me.end, tot, tm);
+    const int l0 = a.group_off[g], l1 = a.group_off[g + 1];
+    double group_sumsq = 0.0;
+    if (threadIdx.x == 0) is_last = n_subs;      // 1: this block is the group's only one
+    __syncthreads();
+    if (is_last == 1) {
+        // one sub-block, hence at most one layer: no exchange with other blocks
+        if (threadIdx.x == 0 && me.layer >= 0) {
+            double *o = a.stats + (int64_t)me.layer * 3;
+            o[0] = tot;
+            o[1] = sqrt(tot);
+            o[2] = (double)__uint_as_float(tm);   // NaN bits stay NaN
+            group_sumsq = tot;
+        }
+    } else {
+        __syncthreads();                                        // everyone has read is_last
+        if (threadIdx.x == 0) {
+            a.sub_sumsq[blockIdx.x] = tot;
+            a.sub_absmax[blockIdx.x] = tm;
+            __threadfence();                                    // publish the sub-partial
+            const int ticket = atomicAdd(&a.group_ticket[g], 1);
+            is_last = ticket == n_subs - 1;
+        }
+        __syncthreads();
+        if (!is_last) return;
+        __threadfence();                                        // see the other blocks' sub-partials
+        // The group's norm is the l2-norm over all weights of its layers: the
+        // layers' sums of squares added in index order.
+        for (int l = l0; l < l1; ++l) {
+            reduce_partials(a.sub_sumsq, a.sub_absmax, a.layer_sub_off[l], a.layer_sub_off[l + 1], tot,
+                            tm);
+            if (threadIdx.x == 0) {
+                double *o = a.stats + (int64_t)l * 3;
+                o[0] = tot;
+                o[1] = sqrt(tot);
+                o[2] = (double)__uint_as_float(tm);
+                group_sumsq += tot;
+            }
+        }
+        if (threadIdx.x == 0) a.group_ticket[g] = 0;            // ready for the next launch
+    }
+    if (threadIdx.x != 0) return;
+    const double now = sqrt(group_sumsq);
+    if (seen != 0) {                        // the first batch only records its norm
+        const double delta =
+            prev == 0.0 ? (now == 0.0 ? 0.0 : __builtin_huge_val()) : (now - prev) / prev;
+        if (delta < a.T) ++counter;
+        if (counter == a.interval) {
+            bits += a.n_bits;
+            if (bits > 32) bits = 32;
+            counter = 0;
+        }
+        a.counter[g] = counter;
+        a.bits[g] = bits;
+    }
+    a.l2_prev[g] = now;
+    const int r = (bits + 7) >> 3;
+    bool moved = false;
+    for (int l = l0; l < l1; ++l) {
+        if (r != (int)a.rbytes[l]) {
+            a.rbytes[l] = (uint8_t)r;
+            moved = true;
+        }
+    }
+    if (moved) *a.changed = 1;              // benign race: every writer stores 1
+}
+
+// Stream offsets of the current byte counts: exclusive prefix sum of n_l * r_l
+// over the layers into out[0..n_layers] (global or LDS), by one block of
+// `threads` threads (a multiple of 64, at most 1024).  Ends with a barrier.
+__device__ __forceinline__ void block_prefix_pack_off(const int64_t *__restrict__ elem_off,
+                                                      const uint8_t *__restrict__ rbytes,
+                                                      int n_layers, int threads, int64_t *out) {
+    __shared__ long long carry;
+    __shared__ long long wave_total[kFinalWaves];
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < n_layers; base += threads) {
+        const int l = base + tid;
+        long long size = 0;
+        if (l < n_layers) size = (long long)(elem_off[l + 1] - elem_off[l]) * (int)rbytes[l];
+        long long incl = size;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const long long o = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += o;
+        }
+        if (lane == kWave - 1) wave_total[wave] = incl;
+        __syncthreads();
+        long long before = carry;
+        for (int w = 0; w < wave; ++w) before += wave_total[w];
+        if (l < n_layers) out[l] = before + incl - size;
+        __syncthreads();
+        if (tid == threads - 1) carry = before + incl;
+        __syncthreads();
+    }
+    if (tid == 0) out[n_layers] = carry;
+    __syncthreads();
+}
+
+// Plans with more layers than the redo kernel's LDS table holds: the stream
+// offsets are rebuilt in global memory by this one-block kernel instead.
+__global__ __launch_bounds__(kFinalBlock) void prefix_kernel(const FusedArgs a, int64_t *pack_off,
+                                                             int64_t *packed_size) {
     if (*a.changed == 0) return;
+    block_prefix_pack_off(a.elem_off, a.rbytes, a.n_layers, kFinalBlock, pack_off);
+    if (threadIdx.x == 0) *packed_size = pack_off[a.n_layers];
+}
+
+// Redo pass: does nothing unless the rule changed a byte count.  LDS_TABLE:
+// every block computes the new stream offsets into LDS for itself and block 0
+// also stores them for the batches to come; otherwise they were rebuilt in
+// global memory by prefix_kernel.
+template <int OUT, bool LDS_TABLE>
+__global__ __launch_bounds__(kBlock) void redo_kernel(const FusedArgs a, int64_t *pack_off_out,
+                                                      int64_t *packed_size_out,
+                                                      int32_t *steps_done) {
+    __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
+    __shared__ int64_t lds_pack_off[LDS_TABLE ? kRedoLdsLayers + 1 : 1];
+    if (blockIdx.x == 0 && threadIdx.x == 0) *steps_done = 1;   // a batch has been seen
+    if (*a.changed == 0) return;
+    const int64_t *pack_off = a.pack_off;
+    if (LDS_TABLE) {
+        block_prefix_pack_off(a.elem_off, a.rbytes, a.n_layers, kBlock, lds_pack_off);
+        if (blockIdx.x == 0) {
+            for (int l = (int)threadIdx.x; l <= a.n_layers; l += kBlock) pack_off_out[l] = lds_pack_off[l];
+            if (threadIdx.x == 0) *packed_size_out = lds_pack_off[a.n_layers];
+        }
+        pack_off = lds_pack_off;
+    }
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
+    const bool nt = pack_off[a.n_layers] > a.stream_cache_limit;
     for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
         double sum = 0.0;
         uint32_t mag = 0u;
-        fused_block_tile<false, OUT>(a, tile, wave, lane, smem[wave], sum, mag);
+        const BlockTileRef t = find_block_tile(a, tile);
+        fused_block_wave_tile<false, OUT>(a, t, pack_off[t.layer], nt, wave, lane, smem[wave], sum,
+                                          mag);
         wave_lds_sync();     // the slice is reused by the next tile
     }
 }
 
 // Pack and truncate in one kernel from host-built tables (adt_pack_unpack): the
 // weights are read once and both the stream and the words Bitunpack would
-// return are written.
-template <bool INLINE>
-__global__ __launch_bounds__(kBlock) void pack_unpack_kernel(const PackUnpackArgs a) {
-    __shared__ __attribute__((aligned(16))) uint32_t smem[kWavesPerBlock][kWaveLdsDw];
+// return are written.  Blocks of WAVES wavefronts, one wave tile per wave.
+template <bool INLINE, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void pack_unpack_kernel(const PackUnpackArgs a) {
+    __shared__ __attribute__((aligned(16))) uint32_t smem[WAVES][kWaveLdsDw];
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
-    const TileRef t = locate<INLINE>(a.p, blockIdx.x, wave);
+    const TileRef t = locate<INLINE, WAVES>(a.p, blockIdx.x, wave);
     if (t.len == 0) return;
     const uint32_t *src = a.p.weights + t.elem;
     uint8_t *stream = a.p.packed + t.byte;
@@ -186,110 +348,74 @@ __global__ __launch_bounds__(kBlock) void pack_unpack_kernel(const PackUnpackArg
     }
 }
 
-// Algorithm 1 for all layers, then the stream offsets of the new byte counts.
-constexpr int kRuleBlock = 1024;
-constexpr int kRuleWaves = kRuleBlock / kWave;
-
-__global__ __launch_bounds__(kRuleBlock) void rule_kernel(const RuleArgs a) {
-    __shared__ int any_changed;
-    __shared__ long long carry;
-    __shared__ long long wave_total[kRuleWaves];
-    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const bool is_first = *a.steps_done == 0;   // read by all before thread 0 bumps it at the end
-    if (tid == 0) {
-        any_changed = 0;
-        carry = 0;
-    }
-    __syncthreads();
-    // Phase 1: one thread per group.  The group's norm is the l2-norm over all
-    // weights of its layers (sum of the layers' sums of squares, index order).
-    for (int g = tid; g < a.n_groups; g += kRuleBlock) {
-        const int l0 = a.group_off[g], l1 = a.group_off[g + 1];
-        double sumsq = 0.0;
-        for (int l = l0; l < l1; ++l) sumsq += a.stats[3 * l];
-        const double now = sqrt(sumsq);
-        int bits = a.bits[g];
-        if (!is_first) {
-            const double prev = a.l2_prev[g];
-            const double delta =
-                prev == 0.0 ? (now == 0.0 ? 0.0 : __builtin_huge_val()) : (now - prev) / prev;
-            int counter = a.counter[g];
-            if (delta < a.T) ++counter;
-            if (counter == a.interval) {
-                bits += a.n_bits;
-                if (bits > 32) bits = 32;
-                counter = 0;
-            }
-            a.counter[g] = counter;
-            a.bits[g] = bits;
-        }
-        a.l2_prev[g] = now;
-        const int r = (bits + 7) >> 3;
-        for (int l = l0; l < l1; ++l) {
-            if (r != (int)a.rbytes[l]) {
-                a.rbytes[l] = (uint8_t)r;
-                any_changed = 1;      // benign race: every writer stores 1
-            }
-        }
-    }
-    __syncthreads();
-    // Phase 2: stream offsets = exclusive prefix sum of n_l * r_l over the layers.
-    for (int base = 0; base < a.n_layers; base += kRuleBlock) {
-        const int l = base + tid;
-        long long size = 0;
-        if (l < a.n_layers)
-            size = (long long)(a.elem_off[l + 1] - a.elem_off[l]) * (int)a.rbytes[l];
-        // exclusive prefix sum of `size` over the block, on top of `carry`
-        long long incl = size;
-#pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            const long long o = __shfl_up(incl, off, kWave);
-            if (lane >= off) incl += o;
-        }
-        if (lane == kWave - 1) wave_total[wave] = incl;
-        __syncthreads();
-        long long before = carry;
-        for (int w = 0; w < wave; ++w) before += wave_total[w];
-        if (l < a.n_layers) a.pack_off[l] = before + incl - size;
-        __syncthreads();
-        if (tid == kRuleBlock - 1) carry = before + incl;
-        __syncthreads();
-    }
-    if (tid == 0) {
-        a.pack_off[a.n_layers] = carry;
-        *a.packed_size = carry;
-        *a.changed = any_changed;
-        *a.steps_done = 1;
-    }
+template <int WAVES>
+static hipError_t launch_fused_w(const FusedArgs &a, int out_format, uint32_t extra_lds,
+                                 hipStream_t stream) {
+    void (*k)(FusedArgs) = out_format == kOutNone   ? fused_kernel<kOutNone, WAVES>
+                           : out_format == kOutFp32 ? fused_kernel<kOutFp32, WAVES>
+                           : out_format == kOutBf16 ? fused_kernel<kOutBf16, WAVES>
+                                                    : fused_kernel<kOutFp16, WAVES>;
+    return launch(k, kKernelFused, a.n_tiles * (uint32_t)(kWavesPerBlock / WAVES), WAVES * kWave,
+                  stream, a, extra_lds);
 }
 
-// out_format: kOutNone, kOutFp32, kOutBf16 or kOutFp16
-hipError_t launch_fused(const FusedArgs &a, int out_format, hipStream_t stream) {
-    void (*k)(FusedArgs) = out_format == kOutNone   ? fused_kernel<kOutNone>
-                           : out_format == kOutFp32 ? fused_kernel<kOutFp32>
-                           : out_format == kOutBf16 ? fused_kernel<kOutBf16>
-                                                    : fused_kernel<kOutFp16>;
-    return launch(k, kKernelFused, a.n_tiles, kBlock, stream, a);
+// out_format: kOutNone, kOutFp32, kOutBf16 or kOutFp16; waves: 1 or 4
+hipError_t launch_fused(const FusedArgs &a, int out_format, int waves, uint32_t extra_lds,
+                        hipStream_t stream) {
+    return waves == 1 ? launch_fused_w<1>(a, out_format, extra_lds, stream)
+                      : launch_fused_w<4>(a, out_format, extra_lds, stream);
 }
 
-hipError_t launch_redo(const FusedArgs &a, int out_format, hipStream_t stream) {
-    const uint32_t grid = a.n_tiles < 1024u ? a.n_tiles : 1024u;
-    void (*k)(FusedArgs) = out_format == kOutNone   ? redo_kernel<kOutNone>
-                           : out_format == kOutFp32 ? redo_kernel<kOutFp32>
-                           : out_format == kOutBf16 ? redo_kernel<kOutBf16>
-                                                    : redo_kernel<kOutFp16>;
-    return launch(k, kKernelRedo, grid, kBlock, stream, a);
+hipError_t launch_final_rule(const FinalRuleArgs &a, hipStream_t stream) {
+    return a.n_subs <= kFinalInlineSubs
+               ? launch(final_rule_kernel<true>, kKernelFinalRule, (uint32_t)a.n_subs, kFinalBlock,
+                        stream, a)
+               : launch(final_rule_kernel<false>, kKernelFinalRule, (uint32_t)a.n_subs, kFinalBlock,
+                        stream, a);
 }
 
+template <typename... A>
+static hipError_t launch_plain(void (*kernel)(A...), int kernel_id, uint32_t grid, int block,
+                               hipStream_t stream, A... args) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (timing_events(kernel_id, stream, &e0, &e1))
+        hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(block), 0, stream, e0, e1, 0, args...);
+    else
+        kernel<<<dim3(grid), dim3(block), 0, stream>>>(args...);
+    return hipGetLastError();
+}
+
+hipError_t launch_redo(const FusedArgs &a, int out_format, int64_t *pack_off, int64_t *packed_size,
+                       int32_t *steps_done, hipStream_t stream) {
+    const bool lds_table = a.n_layers <= kRedoLdsLayers;
+    if (!lds_table) {
+        hipError_t e = launch_plain(prefix_kernel, kKernelPrefix, 1u, kFinalBlock, stream, a, pack_off,
+                                    packed_size);
+        if (e != hipSuccess) return e;
+    }
+    uint32_t grid = a.n_tiles < (uint32_t)kRedoBlocks ? a.n_tiles : (uint32_t)kRedoBlocks;
+    if (grid == 0) grid = 1;
+    void (*k)(FusedArgs, int64_t *, int64_t *, int32_t *);
+    if (lds_table)
+        k = out_format == kOutNone   ? redo_kernel<kOutNone, true>
+            : out_format == kOutFp32 ? redo_kernel<kOutFp32, true>
+            : out_format == kOutBf16 ? redo_kernel<kOutBf16, true>
+                                     : redo_kernel<kOutFp16, true>;
+    else
+        k = out_format == kOutNone   ? redo_kernel<kOutNone, false>
+            : out_format == kOutFp32 ? redo_kernel<kOutFp32, false>
+            : out_format == kOutBf16 ? redo_kernel<kOutBf16, false>
+                                     : redo_kernel<kOutFp16, false>;
+    return launch_plain(k, kKernelRedo, grid, kBlock, stream, a, pack_off, packed_size, steps_done);
+}
+
+// waves: 1 or 4 (the tile table must have been built for waves * 1024 weights per block)
 hipError_t launch_pack_unpack(const PackUnpackArgs &a, uint32_t n_tiles, bool inline_table,
-                              hipStream_t stream) {
-    return inline_table
-               ? launch(pack_unpack_kernel<true>, kKernelPackUnpack, n_tiles, kBlock, stream, a)
-               : launch(pack_unpack_kernel<false>, kKernelPackUnpack, n_tiles, kBlock, stream, a);
-}
-
-hipError_t launch_rule(const RuleArgs &a, hipStream_t stream) {
-    return launch(rule_kernel, kKernelRule, 1u, kRuleBlock, stream, a);
+                              int waves, uint32_t extra_lds, hipStream_t stream) {
+    void (*k)(PackUnpackArgs);
+    if (waves == 1) k = inline_table ? pack_unpack_kernel<true, 1> : pack_unpack_kernel<false, 1>;
+    else k = inline_table ? pack_unpack_kernel<true, 4> : pack_unpack_kernel<false, 4>;
+    return launch(k, kKernelPackUnpack, n_tiles, waves * kWave, stream, a, extra_lds);
 }
 
 }  // namespace adt

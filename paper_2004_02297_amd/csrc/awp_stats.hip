@@ -18,35 +18,12 @@
 
 #include "adt_launch.h"
 #include "adt_tables.h"
+#include "awp_partials.h"
 
 namespace adt {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
-
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;   // every lane holds the same value
-}
-
-__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const uint32_t o = (uint32_t)__shfl_xor((int)v, off, kWave);
-        v = o > v ? o : v;
-    }
-    return v;
-}
-
-// Magnitude bits: ordering them as unsigned integers orders finite values and
-// infinity by magnitude and puts every NaN above infinity, so a NaN wins.
-__device__ __forceinline__ void accumulate(uint32_t bits, double &acc, uint32_t &mag) {
-    const double w = (double)__uint_as_float(bits);
-    acc = fma(w, w, acc);
-    const uint32_t m = bits & 0x7FFFFFFFu;
-    mag = m > mag ? m : mag;
-}
 
 __device__ __forceinline__ void block_combine(double sum, uint32_t mag, double *out_sum,
                                               uint32_t *out_mag) {
@@ -77,11 +54,11 @@ __global__ __launch_bounds__(kBlock) void stats_partial_kernel(const StatsArgs a
     int lo = 0, hi = a.n_layers;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
-        if (tile_off[mid] <= block) lo = mid; else hi = mid;
+        if (table_load(tile_off, mid) <= block) lo = mid; else hi = mid;
     }
-    const int64_t e_begin = elem_off[lo];
-    const int64_t first = (int64_t)(block - tile_off[lo]) * kStatsTile;
-    const int64_t left = (elem_off[lo + 1] - e_begin) - first;   // > 0 by construction
+    const int64_t e_begin = table_load(elem_off, lo);
+    const int64_t first = (int64_t)(block - table_load(tile_off, lo)) * kStatsTile;
+    const int64_t left = (table_load(elem_off, lo + 1) - e_begin) - first;   // > 0 by construction
     const int len = left < kStatsTile ? (int)left : kStatsTile;
     const uint32_t *src = a.weights + e_begin + first;
     const int tid = (int)threadIdx.x;
@@ -97,10 +74,10 @@ __global__ __launch_bounds__(kBlock) void stats_partial_kernel(const StatsArgs a
                 v[j] = __builtin_nontemporal_load((const u32x4_a4 *)(src + 4 * ((it * 4 + j) * kBlock + tid)));
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                accumulate(v[j].x, acc0, mag);
-                accumulate(v[j].y, acc1, mag);
-                accumulate(v[j].z, acc2, mag);
-                accumulate(v[j].w, acc3, mag);
+                square_add(v[j].x, acc0, mag);
+                square_add(v[j].y, acc1, mag);
+                square_add(v[j].z, acc2, mag);
+                square_add(v[j].w, acc3, mag);
             }
         }
     } else {
@@ -108,14 +85,14 @@ __global__ __launch_bounds__(kBlock) void stats_partial_kernel(const StatsArgs a
             const int e0 = 4 * (i * kBlock + tid);
             if (e0 + 4 <= len) {
                 const u32x4 v = __builtin_nontemporal_load((const u32x4_a4 *)(src + e0));
-                accumulate(v.x, acc0, mag);
-                accumulate(v.y, acc1, mag);
-                accumulate(v.z, acc2, mag);
-                accumulate(v.w, acc3, mag);
+                square_add(v.x, acc0, mag);
+                square_add(v.y, acc1, mag);
+                square_add(v.z, acc2, mag);
+                square_add(v.w, acc3, mag);
             } else {
-                if (e0 < len) accumulate(src[e0], acc0, mag);
-                if (e0 + 1 < len) accumulate(src[e0 + 1], acc1, mag);
-                if (e0 + 2 < len) accumulate(src[e0 + 2], acc2, mag);
+                if (e0 < len) square_add(src[e0], acc0, mag);
+                if (e0 + 1 < len) square_add(src[e0 + 1], acc1, mag);
+                if (e0 + 2 < len) square_add(src[e0 + 2], acc2, mag);
             }
         }
     }
@@ -123,52 +100,14 @@ __global__ __launch_bounds__(kBlock) void stats_partial_kernel(const StatsArgs a
                   &a.partial_absmax[block]);
 }
 
-constexpr int kFinalBlock = 1024;
-constexpr int kFinalWaves = kFinalBlock / kWave;
-
 template <bool INLINE>
 __global__ __launch_bounds__(kFinalBlock) void stats_final_kernel(const StatsFinalArgs a) {
     const uint32_t *tile_off = INLINE ? a.inl_tile_off : a.dev_tile_off;
     const int layer = (int)blockIdx.x;
-    const uint32_t begin = tile_off[layer], end = tile_off[layer + 1];
-    // Thread t adds partials begin+t, begin+t+1024, ... in that order; eight
-    // independent loads are in flight per round.
-    constexpr int kInFlight = 8;
-    double acc = 0.0;
-    uint32_t mag = 0u;
-    for (uint32_t i = begin + threadIdx.x; i < end; i += kInFlight * kFinalBlock) {
-        double v[kInFlight];
-        uint32_t m[kInFlight];
-#pragma unroll
-        for (int j = 0; j < kInFlight; ++j) {
-            const uint32_t k = i + j * kFinalBlock;
-            const bool ok = k < end;
-            v[j] = ok ? a.partial_sumsq[k] : 0.0;
-            m[j] = ok ? a.partial_absmax[k] : 0u;
-        }
-#pragma unroll
-        for (int j = 0; j < kInFlight; ++j) {
-            acc += v[j];
-            mag = m[j] > mag ? m[j] : mag;
-        }
-    }
-    __shared__ double wsum[kFinalWaves];
-    __shared__ uint32_t wmag[kFinalWaves];
-    acc = wave_sum(acc);
-    mag = wave_max(mag);
-    if ((threadIdx.x & 63) == 0) {
-        wsum[threadIdx.x >> 6] = acc;
-        wmag[threadIdx.x >> 6] = mag;
-    }
-    __syncthreads();
+    double tot;
+    uint32_t tm;
+    reduce_partials(a.partial_sumsq, a.partial_absmax, tile_off[layer], tile_off[layer + 1], tot, tm);
     if (threadIdx.x == 0) {
-        double tot = 0.0;
-        uint32_t tm = 0u;
-#pragma unroll
-        for (int i = 0; i < kFinalWaves; ++i) {
-            tot += wsum[i];
-            tm = wmag[i] > tm ? wmag[i] : tm;
-        }
         double *o = a.stats_out + (int64_t)layer * 3;
         o[0] = tot;
         o[1] = sqrt(tot);
@@ -187,13 +126,6 @@ hipError_t launch_stats(const StatsArgs &a, const StatsFinalArgs &f, uint32_t n_
                          a, kStatsExtraLds);
         if (e != hipSuccess) return e;
     }
-    return inline_table ? launch(stats_final_kernel<true>, kKernelStatsFinal, (uint32_t)f.n_layers,
-                                 kFinalBlock, stream, f)
-                        : launch(stats_final_kernel<false>, kKernelStatsFinal,
-                                 (uint32_t)f.n_layers, kFinalBlock, stream, f);
-}
-
-hipError_t launch_stats_final(const StatsFinalArgs &f, bool inline_table, hipStream_t stream) {
     return inline_table ? launch(stats_final_kernel<true>, kKernelStatsFinal, (uint32_t)f.n_layers,
                                  kFinalBlock, stream, f)
                         : launch(stats_final_kernel<false>, kKernelStatsFinal,

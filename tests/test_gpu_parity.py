@@ -296,7 +296,68 @@ def test_stats_misaligned_base_and_determinism(adt):
     assert outs[0].tobytes() == outs[1].tobytes()      # independent of base alignment
 
 
+@pytest.mark.parametrize("kernel", ["pack_kernel", "pack_unpack_kernel"])
+@pytest.mark.parametrize("waves,extra_lds", [(1, 0), (1, 9216), (4, 20480)])
+def test_launch_shapes_of_pack_give_the_same_bytes(adt, kernel, waves, extra_lds):
+    off, rb, w = workloads.alignment_sweep_case()
+    sizes = [1, 1023, 1024, 1025, 4095, 4096, 4097, 0, 20000, 3]
+    off2, rb2, w2 = workloads.ragged_case(sizes, [1, 2, 3, 4, 3, 2, 1, 4, 3, 2], seed=61)
+    try:
+        adt.adt_launch_shape(kernel, waves, extra_lds)
+        for o, r, x in ((off, rb, w), (off2, rb2, w2)):
+            check_pack_unpack(adt, x, o, r, 1, 5)
+            check_pack_unpack_fused(adt, x, o, r, 3, 11)
+    finally:
+        adt.adt_launch_shape(kernel, 0)
+    with pytest.raises(adt.AdtError):
+        adt.adt_launch_shape("pack_kernel", 2)
+    with pytest.raises(adt.AdtError):
+        adt.adt_launch_shape("unpack_kernel", 4)
+    with pytest.raises(adt.AdtError):
+        adt.adt_launch_shape("stats_partial_kernel", 1)
+
+
+@pytest.mark.parametrize("kernel", ["pack_kernel", "pack_unpack_kernel"])
+def test_stream_store_kind_does_not_change_the_bytes(adt, kernel):
+    """Ordinary and nontemporal stream stores (chosen by the stream's size against a
+    limit) write the same bytes, aligned or not."""
+    off, rb, w = workloads.alignment_sweep_case()
+    old = adt.adt_stream_cache_limit(kernel)
+    try:
+        for limit in (0, 1 << 60):
+            adt.adt_stream_cache_limit(kernel, limit)
+            check_pack_unpack(adt, w, off, rb, 0, 0)
+            check_pack_unpack(adt, w, off, rb, 1, 9)
+            check_pack_unpack_fused(adt, w, off, rb, 0, 0)
+            check_pack_unpack_fused(adt, w, off, rb, 2, 5)
+    finally:
+        adt.adt_stream_cache_limit(kernel, old)
+    with pytest.raises(adt.AdtError):
+        adt.adt_stream_cache_limit("unpack_kernel", 0)
+
+
 # ------------------------------------------------------------------ streams
+def test_statistics_calls_on_two_streams_share_the_scratch_safely(adt):
+    """awp_layer_stats keeps one scratch buffer per device; calls on different
+    streams are ordered against each other by the library."""
+    a = workloads.make_weight_set("alexnet")
+    b = workloads.make_weight_set("resnet50")
+    da, db = dev(a.weights), dev(b.weights)
+    ea, eb = oracle.stats(a.weights, a.layer_offsets), oracle.stats(b.weights, b.layer_offsets)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    outs = []
+    for _ in range(6):
+        with torch.cuda.stream(s1):
+            outs.append((adt.awp_layer_stats(da, a.layer_offsets), ea))
+        with torch.cuda.stream(s2):
+            outs.append((adt.awp_layer_stats(db, b.layer_offsets), eb))
+    torch.cuda.synchronize()
+    for got, exp in outs:
+        np.testing.assert_allclose(got.cpu().numpy(), exp, rtol=STATS_RTOL, atol=0.0)
+
+
+
 def test_non_default_stream(adt):
     ws = workloads.make_weight_set("tiny")
     rb = workloads.config_bytes("tiny")

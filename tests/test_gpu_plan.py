@@ -157,24 +157,143 @@ def test_plan_resnet34_block_groups_full_size(adt):
     plan.close()
 
 
-def test_plan_full_size_vgg16(adt):
+@pytest.mark.parametrize("variant,out_dtype", [
+    ("all2", torch.float32), ("all3", torch.float32), ("all4", torch.float32),
+    ("mixed", torch.float32), ("all3", torch.bfloat16), ("mixed", torch.float16),
+])
+def test_plan_full_size_vgg16(adt, variant, out_dtype):
+    """The whole pass on the VGG-16-shaped set at every byte assignment the
+    measurements use, with the default (nontemporal) stream stores."""
     ws = workloads.make_weight_set("vgg16")
     off, N, L = ws.layer_offsets, ws.n_weights, ws.n_layers
+    rb = workloads.config_bytes("vgg16", variant)
+    size = oracle.packed_size(off, rb)
     w = torch.from_numpy(ws.weights).cuda()
     packed = torch.empty(4 * N, dtype=torch.uint8, device="cuda")
-    out = torch.empty_like(w)
-    plan = adt.AwpPlan(off, -2e-3, 4000, 8, init_bits=np.full(L, 16, np.int32))
+    out = torch.empty(N, dtype=out_dtype, device="cuda")
+    plan = adt.AwpPlan(off, -2e-3, 4000, 8, init_bits=rb.astype(np.int32) * 8)
     for _ in range(3):
         plan.step(w, packed, out)
     got = plan.read()
-    rb = np.full(L, 2, np.uint8)
     assert np.array_equal(got["bytes"], rb)
     np.testing.assert_allclose(got["stats"], oracle.stats(ws.weights, off), rtol=1e-10)
     exp = oracle.pack(ws.weights, off, rb)
-    assert got["packed_size"] == exp.size
+    assert got["packed_size"] == exp.size == size
     assert np.array_equal(packed[:exp.size].cpu().numpy(), exp)
-    assert np.array_equal(out.view(torch.int32).cpu().numpy(),
-                          oracle.unpack(exp, off, rb).view(np.int32))
+    if out_dtype == torch.float32:
+        assert np.array_equal(out.view(torch.int32).cpu().numpy(),
+                              oracle.unpack(exp, off, rb).view(np.int32))
+    else:
+        fmt = "bf16" if out_dtype == torch.bfloat16 else "fp16"
+        assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16),
+                              oracle.unpack16(exp, off, rb, fmt))
+    plan.close()
+
+
+def test_plan_full_size_stream_crosses_the_cache_limit_inside_a_redo(adt):
+    """VGG-16-shaped weights whose norms shrink every batch, so that with T = 0 and
+    INTERVAL = 1 every layer gains a byte per batch: 1 -> 2 -> 3 -> 4 bytes.  The
+    stream grows from 132 MiB to 528 MiB.  With the limit of the cache-friendly
+    stream stores set to 280 MiB, the batch that takes the stream from 264 to
+    396 MiB crosses it inside the redo pass (the speculative pass of that batch
+    still ran below the limit)."""
+    ws = workloads.make_weight_set("vgg16")
+    off, N, L = ws.layer_offsets, ws.n_weights, ws.n_layers
+    limit = 280 << 20
+    old = adt.adt_stream_cache_limit("fused_kernel", limit)
+    try:
+        hw = ws.weights.copy()
+        w = torch.from_numpy(hw).cuda()
+        packed = torch.empty(4 * N, dtype=torch.uint8, device="cuda")
+        out = torch.empty_like(w)
+        plan = adt.AwpPlan(off, 0.0, 1, 8)
+        ost = oracle.AwpState(L, 8)
+        sizes = []
+        for step in range(5):
+            if step:
+                hw *= np.float32(0.99)
+                w.copy_(torch.from_numpy(hw))
+            plan.step(w, packed, out)
+            got = plan.read()
+            o_stats = oracle.stats(hw, off)
+            orb = oracle.awp_update(ost, o_stats[:, 1], 0.0, 1, 8)
+            assert np.array_equal(got["bytes"], orb), step
+            exp = oracle.pack(hw, off, orb)
+            assert got["packed_size"] == exp.size
+            assert np.array_equal(packed[:exp.size].cpu().numpy(), exp), step
+            assert np.array_equal(out.view(torch.int32).cpu().numpy(),
+                                  oracle.unpack(exp, off, orb).view(np.int32)), step
+            sizes.append(exp.size)
+    finally:
+        adt.adt_stream_cache_limit("fused_kernel", old)
+    assert sizes == [N, 2 * N, 3 * N, 4 * N, 4 * N]
+    assert sizes[1] <= limit < sizes[2]
+    plan.close()
+
+
+def test_plan_cache_limit_flips_between_batches_small(adt):
+    """The same flip on a small ragged set, with the limit lowered so that the
+    stream crosses it back and forth: the bytes never depend on the store kind."""
+    old = adt.adt_stream_cache_limit("fused_kernel")
+    try:
+        for limit in (0, 60000, 1 << 60):
+            adt.adt_stream_cache_limit("fused_kernel", limit)
+            n = run_trajectory(adt, [5000, 4097, 1, 12289, 0, 3000], steps=10, T=0.0, interval=1,
+                               n_bits=8, init_bits=None, seed=11, w_shift=1, p_shift=7)
+            assert n >= 3
+    finally:
+        adt.adt_stream_cache_limit("fused_kernel", old)
+
+
+@pytest.mark.parametrize("waves,extra_lds", [(1, 0), (1, 12288), (4, 0), (4, 24576)])
+def test_plan_launch_shapes_give_identical_results(adt, waves, extra_lds):
+    """Every launch shape of the fused kernel (1 or 4 wavefronts per block, with or
+    without an occupancy cap) gives the oracle's bytes and the default shape's
+    statistics bit for bit."""
+    sizes = [1, 0, 5, 4095, 4096, 4097, 17, 12289, 1023, 30000, 3, 8192, 1025, 2049, 3073]
+    off = workloads.offsets_from_sizes(sizes)
+    N = int(off[-1])
+    hw = workloads.ragged_case(sizes, [1] * len(sizes), seed=77, he=True)[2]
+    w = torch.from_numpy(hw).cuda()
+    packed = torch.empty(4 * N, dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(w)
+    ref = adt.AwpPlan(off, 0.0, 1, 8)
+    ref.step(w, packed, out)
+    want = ref.read()["stats"]
+    ref.close()
+    try:
+        adt.adt_launch_shape("fused_kernel", waves, extra_lds)
+        n = run_trajectory(adt, sizes, steps=8, T=0.0, interval=1, n_bits=8, init_bits=None,
+                           seed=12, w_shift=1, p_shift=3)
+        assert n >= 2
+        plan = adt.AwpPlan(off, 0.0, 1, 8)
+        plan.step(w, packed, out)
+        assert plan.read()["stats"].tobytes() == want.tobytes()
+        plan.close()
+    finally:
+        adt.adt_launch_shape("fused_kernel", 0)
+
+
+def test_plan_more_layers_than_the_redo_table_holds(adt):
+    """Beyond 4096 layers the stream offsets are rebuilt by a kernel of their own."""
+    rng = np.random.default_rng(19)
+    sizes = rng.integers(0, 400, size=5000).tolist()
+    n = run_trajectory(adt, sizes, steps=5, T=0.0, interval=1, n_bits=8, init_bits=None, seed=14)
+    assert n >= 1
+
+
+def test_plan_with_only_empty_layers(adt):
+    off = np.zeros(4, dtype=np.int64)
+    plan = adt.AwpPlan(off, 0.0, 1, 8)
+    z = torch.zeros(0, dtype=torch.float32, device="cuda")
+    p = torch.zeros(0, dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        plan.step(z, p, None)
+    got = plan.read()
+    # zero norms: delta = 0, not below T = 0, nothing is ever counted
+    assert got["bits"].tolist() == [8, 8, 8] and got["counter"].tolist() == [0, 0, 0]
+    assert got["packed_size"] == 0 and got["stats"].tolist() == [[0.0] * 3] * 3
+    assert plan.get_state()["batches_seen"] == 1
     plan.close()
 
 
@@ -243,6 +362,45 @@ def test_plan_step_replayed_from_a_hip_graph(adt):
     assert changes >= 2
     eager.close()
     graphed.close()
+
+
+def test_launch_timing_stays_out_of_a_captured_graph(adt):
+    """With launch timing switched on, a step captured into a graph is recorded as
+    ordinary launches (timing events inside a capture would never complete); the
+    replays are correct and adt_timing_read returns without blocking."""
+    sizes = [5000, 4096, 77]
+    off = workloads.offsets_from_sizes(sizes)
+    N = int(off[-1])
+    hw = workloads.ragged_case(sizes, [1] * 3, seed=5, he=True)[2]
+    w = torch.from_numpy(hw).cuda()
+    p = torch.zeros(4 * N, dtype=torch.uint8, device="cuda")
+    o = torch.zeros(N, dtype=torch.float32, device="cuda")
+    plan = adt.AwpPlan(off, -1.0, 5, 8, init_bits=np.full(3, 16, np.int32))
+    torch.cuda.synchronize()
+    adt.adt_timing_enable(True, 16)
+    adt.adt_timing_read()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            plan.step(w, p, o)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    assert all(v["launches"] == 0 for v in adt.adt_timing_read().values())
+    for _ in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+    plan.step(w, p, o)                       # an eager step is timed as usual
+    torch.cuda.synchronize()
+    t = adt.adt_timing_read()
+    adt.adt_timing_enable(False)
+    assert t["fused_kernel"]["launches"] == 1 and t["final_rule_kernel"]["launches"] == 1
+    rb = np.full(3, 2, np.uint8)
+    exp = oracle.pack(hw, off, rb)
+    assert np.array_equal(p[:exp.size].cpu().numpy(), exp)
+    assert np.array_equal(o.view(torch.int32).cpu().numpy(), oracle.unpack(exp, off, rb).view(np.int32))
+    plan.close()
 
 
 def test_plan_checkpoint_and_resume(adt):
