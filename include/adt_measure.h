@@ -38,9 +38,10 @@ const char *adt_kernel_name(int kernel);   /* "" outside 0..ADT_NKERNELS-1 */
  * Launch shape of a streaming kernel (tuning aid): wavefronts per block and a
  * number of bytes of dynamic LDS that the kernel never touches, which lowers
  * the number of blocks a compute unit holds at once.  kernel: the index of
- * "pack_kernel", "unpack_kernel", "pack_unpack_kernel" or "fused_kernel"
- * (adt_kernel_name); waves: 1 or 4 (unpack_kernel: 1), or 0 to return to the
- * library's own choice.  Results do not depend on the shape, bit for bit.
+ * "pack_kernel", "unpack_kernel", "pack_unpack_kernel", "fused_kernel" or
+ * "stats_partial_kernel" (adt_kernel_name); waves: 1 or 4 (unpack_kernel: 1,
+ * stats_partial_kernel: 4), or 0 to return to the library's own choice.
+ * Results do not depend on the shape, bit for bit.
  */
 int adt_launch_shape(int kernel, int waves, int extra_lds_bytes);
 

@@ -26,7 +26,7 @@ hipError_t launch_pack(const PackArgs &a, uint32_t n_tiles, bool inline_table, i
 hipError_t launch_unpack(const PackArgs &a, uint32_t n_tiles, bool inline_table, int out_format,
                          uint32_t extra_lds, hipStream_t stream);
 hipError_t launch_stats(const StatsArgs &a, const StatsFinalArgs &f, uint32_t n_tiles,
-                        bool inline_table, hipStream_t stream);
+                        bool inline_table, uint32_t extra_lds, hipStream_t stream);
 hipError_t launch_fused(const FusedArgs &a, int out_format, int waves, uint32_t extra_lds,
                         hipStream_t stream);
 hipError_t launch_final_rule(const FinalRuleArgs &a, hipStream_t stream);
@@ -527,7 +527,8 @@ int awp_layer_stats(const float *weights, const int64_t *layer_offsets, int n_la
         e = hipMemcpyAsync(slot->dev, slot->host, bytes, hipMemcpyHostToDevice, hs);
         if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(table)");
     }
-    e = adt::launch_stats(a, f, n_tiles, inl, hs);
+    e = adt::launch_stats(a, f, n_tiles, inl,
+                          shape_of(adt::kKernelStatsPartial, adt::stats_shape()).extra_lds, hs);
     if (!inl) {
         if (hipEventRecord(slot->ev, hs) == hipSuccess) slot->pending = true;
         else (void)hipStreamSynchronize(hs);
@@ -592,7 +593,9 @@ int awp_layer_stats_noalloc(const float *weights, const int64_t *layer_offsets, 
     f.partial_absmax = a.partial_absmax;
     f.stats_out = stats_out;
     f.n_layers = n_layers;
-    hipError_t e = adt::launch_stats(a, f, n_tiles, true, (hipStream_t)stream);
+    hipError_t e = adt::launch_stats(
+        a, f, n_tiles, true, shape_of(adt::kKernelStatsPartial, adt::stats_shape()).extra_lds,
+        (hipStream_t)stream);
     if (e != hipSuccess) return fail_hip(e, "statistics launch");
     return ADT_OK;
 }
@@ -1062,13 +1065,17 @@ int64_t adt_stream_cache_limit(int kernel, int64_t bytes) {
 
 int adt_launch_shape(int kernel, int waves, int extra_lds_bytes) {
     const bool ok_kernel = kernel == adt::kKernelPack || kernel == adt::kKernelPackUnpack ||
-                           kernel == adt::kKernelFused || kernel == adt::kKernelUnpack;
+                           kernel == adt::kKernelFused || kernel == adt::kKernelUnpack ||
+                           kernel == adt::kKernelStatsPartial;
     if (!ok_kernel)
-        return fail(ADT_EINVAL, "launch shape: kernel must be pack, unpack, pack_unpack or fused");
-    const bool ok_waves = waves == 0 || waves == 1 || (waves == 4 && kernel != adt::kKernelUnpack);
-    if (!ok_waves) return fail(ADT_EINVAL, "launch shape: waves must be 0, 1 or 4 (unpack: 0 or 1)");
-    if (extra_lds_bytes < 0 || extra_lds_bytes > 48 * 1024)
-        return fail(ADT_EINVAL, "launch shape: extra LDS must be within 0..48 KiB");
+        return fail(ADT_EINVAL,
+                    "launch shape: kernel must be pack, unpack, pack_unpack, fused or stats_partial");
+    const bool ok_waves = waves == 0 || (waves == 1 && kernel != adt::kKernelStatsPartial) ||
+                          (waves == 4 && kernel != adt::kKernelUnpack);
+    if (!ok_waves)
+        return fail(ADT_EINVAL, "launch shape: waves must be 0, 1 or 4 (unpack: 1, stats_partial: 4)");
+    if (extra_lds_bytes < 0 || extra_lds_bytes > 60 * 1024)
+        return fail(ADT_EINVAL, "launch shape: extra LDS must be within 0..60 KiB");
     std::lock_guard<std::mutex> lock(g_shape_mu);
     g_shape[kernel] = LaunchShape{waves, (uint32_t)extra_lds_bytes};
     return ADT_OK;

@@ -48,7 +48,8 @@ constexpr int kStatsTile = kBlock * kStatsLoadsPerLane * 4;
 //                  1-wave, 10 KB           211 / 224 / 248 / 263
 //   pack + unpack  1-wave, 8 / 10 / 12 KB  194 / 217 / 244 / 259 (best of the three)
 //   pack           1-wave, 4 KB            110 / 127 / 151 / 171   (4-wave: 112 / 129 / 152 / 175)
-//   unpack         1-wave, 6 KB / 8 KB     111 / 129 / 155 / 170   (no cap: 129 / 145 / 166 / 180)
+//   unpack         1-wave, 6 KB            111 / 129 / 155 / 170   (no cap: 129 / 145 / 166 / 180;
+//                  right behind pack:      116 / 116 / 155 / 169    no cap: 126 / 119 / 164 / 178)
 // The cap is chosen from the stream's bytes per weight (how write-heavy the
 // launch is).
 struct LaunchShape {
@@ -62,11 +63,10 @@ inline LaunchShape pack_unpack_shape(double bytes_per_weight) {
     return LaunchShape{1, bytes_per_weight <= 1.5 ? 8192u : bytes_per_weight <= 2.6 ? 10240u : 12288u};
 }
 inline LaunchShape pack_shape(double) { return LaunchShape{1, 4096u}; }
-inline LaunchShape unpack_shape(double bytes_per_weight) {
-    return LaunchShape{kUnpackWaves, bytes_per_weight <= 1.5 ? 6144u : 8192u};
-}
-// Statistics: 4-wave blocks, 16 waves per compute unit (76.9 us instead of 79.0 us uncapped).
-constexpr uint32_t kStatsExtraLds = 36864;
+inline LaunchShape unpack_shape(double) { return LaunchShape{kUnpackWaves, 6144u}; }
+// Statistics: 4-wave blocks of 8192 weights, 16 waves per compute unit (78 us for 138 M weights,
+// 79 us uncapped, 81 - 85 us with 12 or fewer waves).
+inline LaunchShape stats_shape() { return LaunchShape{4, 36864u}; }
 
 constexpr int kInlineLayers = 128;
 

@@ -116,14 +116,14 @@ __global__ __launch_bounds__(kFinalBlock) void stats_final_kernel(const StatsFin
 }
 
 hipError_t launch_stats(const StatsArgs &a, const StatsFinalArgs &f, uint32_t n_tiles,
-                        bool inline_table, hipStream_t stream) {
+                        bool inline_table, uint32_t extra_lds, hipStream_t stream) {
     if (n_tiles > 0) {
         hipError_t e =
             inline_table
                 ? launch(stats_partial_kernel<true>, kKernelStatsPartial, n_tiles, kBlock, stream, a,
-                         kStatsExtraLds)
+                         extra_lds)
                 : launch(stats_partial_kernel<false>, kKernelStatsPartial, n_tiles, kBlock, stream,
-                         a, kStatsExtraLds);
+                         a, extra_lds);
         if (e != hipSuccess) return e;
     }
     return inline_table ? launch(stats_final_kernel<true>, kKernelStatsFinal, (uint32_t)f.n_layers,

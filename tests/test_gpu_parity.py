@@ -314,7 +314,7 @@ def test_launch_shapes_of_pack_give_the_same_bytes(adt, kernel, waves, extra_lds
     with pytest.raises(adt.AdtError):
         adt.adt_launch_shape("unpack_kernel", 4)
     with pytest.raises(adt.AdtError):
-        adt.adt_launch_shape("stats_partial_kernel", 1)
+        adt.adt_launch_shape("stats_final_kernel", 4)
 
 
 @pytest.mark.parametrize("kernel", ["pack_kernel", "pack_unpack_kernel"])
