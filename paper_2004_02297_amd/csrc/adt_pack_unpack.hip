@@ -2,9 +2,9 @@
 // arXiv 2004.02297), all layers in one launch.
 //
 // Work decomposition.  A wavefront owns a "wave tile" of 1024 consecutive
-// weights of one layer; four wave tiles make a block tile.  A wave moves its
-// tile in three steps and never talks to another wave, so no block barrier is
-// needed (unpack even runs one wave per block):
+// weights of one layer.  A wave moves its tile in three steps and never talks
+// to another wave, so there is no block barrier and a block may hold one
+// wavefront (the default: see the launch shapes in adt_tables.h) or four:
 //   pack   : 4 coalesced 128-bit loads per lane of FP32 words
 //            -> keep the top r bytes of every word in registers
 //            -> write the r-byte stream to the wave's LDS slice

@@ -216,7 +216,7 @@ struct FinalRuleArgs {
 };
 
 // Redo pass: layers whose stream-offset table fits the kernel's LDS, and its grid.
-constexpr int kRedoLdsLayers = 4096;
-constexpr int kRedoBlocks = 256;
+constexpr int kRedoLdsLayers = 1024;
+constexpr int kRedoBlocks = 1024;
 
 }  // namespace adt

@@ -275,7 +275,7 @@ def test_plan_launch_shapes_give_identical_results(adt, waves, extra_lds):
 
 
 def test_plan_more_layers_than_the_redo_table_holds(adt):
-    """Beyond 4096 layers the stream offsets are rebuilt by a kernel of their own."""
+    """Beyond 1024 layers the stream offsets are rebuilt by a kernel of their own."""
     rng = np.random.default_rng(19)
     sizes = rng.integers(0, 400, size=5000).tolist()
     n = run_trajectory(adt, sizes, steps=5, T=0.0, interval=1, n_bits=8, init_bits=None, seed=14)

@@ -45,38 +45,42 @@ RULE_PINS = [
 
 # (name, text to find, replacement, pins that must notice)
 MUTANTS = [
-    ("pack keeps the LOW bytes", "(word >> (8 * (dropped + k)))", "(word >> (8 * k))", PACK_PINS),
-    ("pack stores bytes most significant first",
-     "Pw[POffset + k] = (uint8_t)((word >> (8 * (dropped + k))) & 0xFFu);",
-     "Pw[POffset + RoundTo - 1 - k] = (uint8_t)((word >> (8 * (dropped + k))) & 0xFFu);", PACK_PINS),
-    ("pack forgets to advance the offset per weight", "            POffset += RoundTo;\n        }\n    }\n    return POffset;\n}\n\n/*\n * Bitunpack",
-     "        }\n        POffset += RoundTo;\n    }\n    return POffset;\n}\n\n/*\n * Bitunpack", PACK_PINS),
-    ("unpack shifts one byte too few", "q << ((4 - RoundTo) * 8)", "q << ((3 - RoundTo) * 8 + (RoundTo == 4 ? 8 : 0))", PACK_PINS),
-    ("unpack assembles bytes in reverse", "q |= (uint32_t)Pw[POffset + k] << (8 * k);",
-     "q |= (uint32_t)Pw[POffset + k] << (8 * (RoundTo - 1 - k));", PACK_PINS),
-    ("unpack fills the low bits with ones", "uint32_t word = q << ((4 - RoundTo) * 8);",
-     "uint32_t word = (q << ((4 - RoundTo) * 8)) | ((RoundTo < 4) ? ((1u << ((4 - RoundTo) * 8)) - 1u) : 0u);", PACK_PINS),
-    ("pack rounds to nearest instead of truncating", "memcpy(&word, &W[i], 4);            /* the weight as a 32-bit word */",
-     "memcpy(&word, &W[i], 4); if (RoundTo < 4 && (word & 0x7F800000u) != 0x7F800000u) word += 1u << ((4 - RoundTo) * 8 - 1);", PACK_PINS),
-    ("squares summed in float", "double w = (double)W[i];\n            sumsq += w * w;\n            if (isnan(w))",
-     "double w = (double)W[i];\n            sumsq += (double)(W[i] * W[i]);\n            if (isnan(w))", STATS_PINS),
-    ("sum of absolute values instead of squares", "sumsq += w * w;\n            if (isnan(w))", "sumsq += fabs(w);\n            if (isnan(w))", STATS_PINS),
-    ("norm without the square root", "stats[layer * ORACLE_NSTATS + 1] = sqrt(sumsq);", "stats[layer * ORACLE_NSTATS + 1] = sumsq;", STATS_PINS),
-    ("largest value instead of largest magnitude", "else if (fabs(w) > absmax) absmax = fabs(w);", "else if (w > absmax) absmax = w;", STATS_PINS),
-    ("last weight of a layer skipped", "for (int64_t i = layer_offsets[layer]; i < layer_offsets[layer + 1]; ++i) {\n            double w",
-     "for (int64_t i = layer_offsets[layer]; i + 1 < layer_offsets[layer + 1]; ++i) {\n            double w", STATS_PINS),
-    ("group norm sums the norms instead of the squares", "            sumsq += w * w;\n        }\n        l2_group[g] = sqrt(sumsq);",
-     "            sumsq += w * w;\n        }\n        l2_group[g] = (group_offsets[g + 1] - group_offsets[g] > 1) ? sumsq : sqrt(sumsq);", STATS_PINS),
-    ("rule compares with <= ", "if (delta < T)", "if (delta <= T)", RULE_PINS),
-    ("rule uses |delta|", "if (delta < T)", "if (fabs(delta) < fabs(T))", RULE_PINS),
-    ("counter resets on a batch that does not count", "if (delta < T)\n                counter[layer] += 1;",
-     "if (delta < T)\n                counter[layer] += 1;\n            else\n                counter[layer] = 0;", RULE_PINS),
-    ("relative change divided by the new norm", "/ l2_prev[layer];", "/ l2_now[layer];", RULE_PINS),
-    ("bits not capped", "if (bits[layer] > 32) bits[layer] = 32;", "", RULE_PINS),
-    ("counter not cleared after an upgrade", "                counter[layer] = 0;\n", "", RULE_PINS),
-    ("bytes rounded down", "(uint8_t)((bits[layer] + 7) / 8)", "(uint8_t)(bits[layer] / 8 ? bits[layer] / 8 : 1)", RULE_PINS),
-    ("first batch already counts", "if (!is_first_batch) {", "if (1) {", RULE_PINS),
-    ("previous norm never updated", "l2_prev[layer] = l2_now[layer];", "if (is_first_batch) l2_prev[layer] = l2_now[layer];", RULE_PINS),
+    ("pack keeps the LOW bytes", "slot[b] = byte_of(word, dropped + b);", "slot[b] = byte_of(word, b);", PACK_PINS),
+    ("pack stores bytes most significant first", "slot[b] = byte_of(word, dropped + b);",
+     "slot[keep - 1 - b] = byte_of(word, dropped + b);", PACK_PINS),
+    ("pack places every weight of a layer at the layer's start",
+     "uint8_t *slot = stream + layer_start + i * keep;\n            for (int b = 0; b < keep; ++b)\n                slot[b] = byte_of",
+     "uint8_t *slot = stream + layer_start;\n            for (int b = 0; b < keep; ++b)\n                slot[b] = byte_of", PACK_PINS),
+    ("pack starts every layer where the previous one started", "layer_start += count * keep;\n    }\n    return layer_start;\n}\n\n/*\n * Bitunpack",
+     "layer_start += (layer + 1 < n_layers) ? 0 : count * keep;\n    }\n    return layer_start;\n}\n\n/*\n * Bitunpack", PACK_PINS),
+    ("unpack shifts one byte too few", "stored << ((4 - keep) * 8)", "stored << ((3 - keep) * 8 + (keep == 4 ? 8 : 0))", PACK_PINS),
+    ("unpack assembles bytes in reverse", "stored |= (uint32_t)slot[b] << (8 * b);",
+     "stored |= (uint32_t)slot[b] << (8 * (keep - 1 - b));", PACK_PINS),
+    ("unpack fills the low bits with ones", "weight_of(stored << ((4 - keep) * 8));",
+     "weight_of((stored << ((4 - keep) * 8)) | ((keep < 4) ? ((1u << ((4 - keep) * 8)) - 1u) : 0u));", PACK_PINS),
+    ("pack rounds to nearest instead of truncating", "const uint32_t word = word_of(layer_weights[i]);",
+     "uint32_t word = word_of(layer_weights[i]); if (keep < 4 && (word & 0x7F800000u) != 0x7F800000u) word += 1u << ((4 - keep) * 8 - 1);", PACK_PINS),
+    ("squares summed in float", "const double w = (double)weights[i];\n        total += w * w;",
+     "const double w = (double)weights[i];\n        total += (double)(weights[i] * weights[i]);", STATS_PINS),
+    ("sum of absolute values instead of squares", "total += w * w;", "total += fabs(w);", STATS_PINS),
+    ("norm without the square root", "row[1] = sqrt(squares);", "row[1] = squares;", STATS_PINS),
+    ("largest value instead of largest magnitude", "const double magnitude = fabs((double)weights[i]);",
+     "const double magnitude = (double)weights[i];", STATS_PINS),
+    ("last weight of a range skipped", "for (int64_t i = first; i < last; ++i) {\n        const double w",
+     "for (int64_t i = first; i + 1 < last; ++i) {\n        const double w", STATS_PINS),
+    ("group norm without the square root for groups of several layers", "l2_group[g] = sqrt(sum_of_squares(weights, first, last));",
+     "l2_group[g] = (group_offsets[g + 1] - group_offsets[g] > 1) ? sum_of_squares(weights, first, last) : sqrt(sum_of_squares(weights, first, last));", STATS_PINS),
+    ("rule compares with <= ", "if (change < threshold)", "if (change <= threshold)", RULE_PINS),
+    ("rule uses the magnitude of the change", "if (change < threshold)", "if (fabs(change) < fabs(threshold))", RULE_PINS),
+    ("count resets on a batch that does not count", "if (change < threshold)\n        layer->counted += 1;",
+     "if (change < threshold)\n        layer->counted += 1;\n    else\n        layer->counted = 0;", RULE_PINS),
+    ("relative change divided by the new norm", "(norm - layer->previous_norm) / layer->previous_norm;",
+     "(norm - layer->previous_norm) / norm;", RULE_PINS),
+    ("bits not capped", "if (layer->bits > 32) layer->bits = 32;", "", RULE_PINS),
+    ("count not cleared after a precision step", "        layer->counted = 0;\n    }\n}", "    }\n}", RULE_PINS),
+    ("bytes rounded down", "(uint8_t)((state.bits + 7) / 8)", "(uint8_t)(state.bits / 8 ? state.bits / 8 : 1)", RULE_PINS),
+    ("first batch already counts", "if (!is_first_batch)\n            awp_layer_step", "if (1)\n            awp_layer_step", RULE_PINS),
+    ("previous norm never updated", "state.previous_norm = l2_now[layer];", "if (is_first_batch) state.previous_norm = l2_now[layer];", RULE_PINS),
 ]
 
 
