@@ -99,7 +99,8 @@ int adt_unpack(const uint8_t *packed, const int64_t *layer_offsets,
  *   ADT_OUT_BF16  the top 16 bits of w'_i (truncation, as ADT itself truncates;
  *                 exact for r <= 2)
  *   ADT_OUT_FP16  w'_i converted to IEEE binary16, round to nearest even,
- *                 overflow to infinity, NaN stays NaN (payload not preserved)
+ *                 overflow to infinity; a NaN becomes the quiet NaN 0x7E00 with
+ *                 the sign of w'_i, whatever its payload
  *   out  device, N 16-bit elements, 2-byte aligned (4-byte alignment of every
  *        layer start is the fast case); must not overlap `packed`
  */

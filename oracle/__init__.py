@@ -113,13 +113,21 @@ def unpack(packed: np.ndarray, layer_offsets, bytes_per_layer) -> np.ndarray:
 def unpack16(packed: np.ndarray, layer_offsets, bytes_per_layer, fmt: str) -> np.ndarray:
     """Bitunpack followed by a conversion to a 16-bit format, as uint16 bit
     patterns: "bf16" keeps the top 16 bits of each unpacked word, "fp16" is the
-    IEEE binary16 value nearest to it (ties to even; numpy's conversion)."""
+    IEEE binary16 value nearest to it (ties to even; numpy's conversion).  A NaN
+    has no nearest value: it becomes the quiet NaN 0x7E00 with the word's sign
+    (the paper proposes half-precision decompression without going into such
+    detail; this is the library header's rule)."""
     w = unpack(packed, layer_offsets, bytes_per_layer)
     if fmt == "bf16":
         return (w.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
     if fmt == "fp16":
-        with np.errstate(over="ignore"):
-            return w.astype(np.float16).view(np.uint16)
+        with np.errstate(over="ignore", invalid="ignore"):
+            half = w.astype(np.float16).view(np.uint16).copy()
+        words = w.view(np.uint32)
+        is_nan = (words & np.uint32(0x7FFFFFFF)) > np.uint32(0x7F800000)
+        sign = ((words >> np.uint32(16)) & np.uint32(0x8000)).astype(np.uint16)
+        half[is_nan] = sign[is_nan] | np.uint16(0x7E00)
+        return half
     raise ValueError("fmt must be 'bf16' or 'fp16'")
 
 

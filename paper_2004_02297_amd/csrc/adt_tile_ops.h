@@ -241,7 +241,7 @@ __device__ __forceinline__ void pack_wave_tile(const uint32_t *__restrict__ src,
 // ---------------------------------------------------------------------------
 constexpr int kOutFp32 = 0;
 constexpr int kOutBf16 = 1;   // top 16 bits of the word (truncation, like ADT itself)
-constexpr int kOutFp16 = 2;   // binary16, round to nearest even, overflow to infinity
+constexpr int kOutFp16 = 2;   // binary16, round to nearest even, overflow to infinity, NaN -> 0x7E00 | sign
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef u32x2 u32x2_a4 __attribute__((aligned(4)));
@@ -249,7 +249,9 @@ typedef u32x2 u32x2_a4 __attribute__((aligned(4)));
 template <int OUT>
 __device__ __forceinline__ uint32_t to_half_bits(uint32_t word) {
     if (OUT == kOutBf16) return word >> 16;
-    return (uint32_t)__half_as_ushort(__float2half_rn(__uint_as_float(word)));
+    const uint32_t half = (uint32_t)__half_as_ushort(__float2half_rn(__uint_as_float(word)));
+    const bool is_nan = (word & 0x7FFFFFFFu) > 0x7F800000u;
+    return is_nan ? (((word >> 16) & 0x8000u) | 0x7E00u) : half;   // one NaN, sign kept
 }
 
 // Store the four unpacked words of chunk starting at tile element e0.

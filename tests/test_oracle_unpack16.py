@@ -51,6 +51,23 @@ def test_fp16_hand_examples():
     assert conv(1.0, 1) == 0x3800                # 1 byte gives 0.5
     assert conv(float("inf"), 1) == 0x7C00       # 2^127 overflows binary16
     assert conv(-0.0, 3) == 0x8000
+    assert conv(float("inf"), 4) == 0x7C00 and conv(float("-inf"), 2) == 0xFC00
+
+
+def test_fp16_nan_rule():
+    """A NaN becomes the quiet NaN 0x7E00 with the word's sign, whatever its payload;
+    a NaN whose payload lies only in the dropped bytes has become an infinity before."""
+    def conv_bits(bits, r):
+        w = np.array([bits], dtype=np.uint32).view(np.float32)
+        off, rb = one_layer(1, r)
+        return int(oracle.unpack16(oracle.pack(w, off, rb), off, rb, "fp16")[0])
+    assert conv_bits(0x7FC00000, 4) == 0x7E00            # the usual quiet NaN
+    assert conv_bits(0xFFC00000, 4) == 0xFE00            # its negative
+    assert conv_bits(0x7F800001, 4) == 0x7E00            # signalling, payload in the lowest bit
+    assert conv_bits(0xFF800001, 4) == 0xFE00
+    assert conv_bits(0x7FFFFFFF, 2) == 0x7E00            # payload survives the cut to 2 bytes
+    assert conv_bits(0x7F800001, 3) == 0x7C00            # payload cut away: an infinity, not a NaN
+    assert conv_bits(0xFF80FF00, 2) == 0xFC00
 
 
 def test_fp16_matches_torch_conversion():
@@ -66,5 +83,7 @@ def test_fp16_matches_torch_conversion():
     got = oracle.unpack16(oracle.pack(w, off, r4), off, r4, "fp16")
     ref = torch.from_numpy(w.copy()).half().view(torch.int16).numpy().view(np.uint16)
     nan = np.isnan(w)
-    assert np.array_equal(got[~nan], ref[~nan])
-    assert np.all((got[nan] & 0x7C00) == 0x7C00) and np.all((got[nan] & 0x03FF) != 0)
+    assert nan.sum() > 100
+    assert np.array_equal(got[~nan], ref[~nan])           # torch's NaN payloads are its own
+    sign = (w.view(np.uint32)[nan] >> 16).astype(np.uint16) & 0x8000
+    assert np.array_equal(got[nan], sign | 0x7E00)
