@@ -449,7 +449,7 @@ class Harness:
 
 
 def run_trajectory(adt, torch, workloads, steps=200):
-    """BASELINE config 5: VGG-16-shaped weights take `steps` steps of a multiplicative
+    """The AWP trajectory: VGG-16-shaped weights take `steps` steps of a multiplicative
     random walk (w += N(0, (1e-3 |w|)^2), generated on the device: input generation,
     outside the library and outside the timed events); every step runs the whole pass
     through the plan with the synthetic AWP parameters T = 0, INTERVAL = 20, N = 8

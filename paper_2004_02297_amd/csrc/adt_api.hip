@@ -826,8 +826,9 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
     a.n_tiles = plan->n_tiles;
 
     if (plan->n_tiles > 0) {
-        const LaunchShape shape =
-            shape_of(adt::kKernelFused, adt::fused_shape(plan->bytes_per_weight_hint));
+        const double out_bytes = out_format == adt::kOutFp32 ? 4.0 : out_format < 0 ? 0.0 : 2.0;
+        const LaunchShape shape = shape_of(
+            adt::kKernelFused, adt::fused_shape(plan->bytes_per_weight_hint + out_bytes));
         e = adt::launch_fused(a, out_format, shape.waves, shape.extra_lds, hs);
         if (e != hipSuccess) return fail_hip(e, "fused launch");
     }

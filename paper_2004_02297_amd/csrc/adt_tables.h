@@ -46,18 +46,25 @@ constexpr int kStatsTile = kBlock * kStatsLoadsPerLane * 4;
 //   fused (plan)   4-wave blocks, no cap   223 / 250 / 283 / 298
 //                  1-wave, 8 KB            199 / 220 / 255 / 273
 //                  1-wave, 10 KB           211 / 224 / 248 / 263
+//   fused, bf16    1-wave, no cap          161 / 187 / 217 / 233
+//   truncated      1-wave, 4 KB            160 / 179 / 210 / 233
+//   weights        1-wave, 8 KB            176 / 189 / 208 / 220
 //   pack + unpack  1-wave, 8 / 10 / 12 KB  194 / 217 / 244 / 259 (best of the three)
 //   pack           1-wave, 4 KB            110 / 127 / 151 / 171   (4-wave: 112 / 129 / 152 / 175)
 //   unpack         1-wave, 6 KB            111 / 129 / 155 / 170   (no cap: 129 / 145 / 166 / 180;
 //                  right behind pack:      116 / 116 / 155 / 169    no cap: 126 / 119 / 164 / 178)
-// The cap is chosen from the stream's bytes per weight (how write-heavy the
+// The cap is chosen from the bytes written per weight (how write-heavy the
 // launch is).
 struct LaunchShape {
     int waves;            // wavefronts per block: 1 or 4
     uint32_t extra_lds;   // bytes of dynamic LDS nothing touches
 };
-inline LaunchShape fused_shape(double bytes_per_weight) {
-    return LaunchShape{1, bytes_per_weight <= 2.5 ? 8192u : 10240u};
+// written_per_weight: stream bytes plus the bytes of a truncated weight (4, 2 or 0)
+inline LaunchShape fused_shape(double written_per_weight) {
+    return LaunchShape{1, written_per_weight <= 4.5   ? 4096u
+                          : written_per_weight <= 5.5 ? 6144u
+                          : written_per_weight <= 6.5 ? 8192u
+                                                      : 10240u};
 }
 inline LaunchShape pack_unpack_shape(double bytes_per_weight) {
     return LaunchShape{1, bytes_per_weight <= 1.5 ? 8192u : bytes_per_weight <= 2.6 ? 10240u : 12288u};
