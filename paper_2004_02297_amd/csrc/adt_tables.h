@@ -46,9 +46,10 @@ constexpr int kStatsTile = kBlock * kStatsLoadsPerLane * 4;
 //   fused (plan)   4-wave blocks, no cap   223 / 250 / 283 / 298
 //                  1-wave, 8 KB            199 / 220 / 255 / 273
 //                  1-wave, 10 KB           211 / 224 / 248 / 263
-//   fused, bf16    1-wave, no cap          161 / 187 / 217 / 233
-//   truncated      1-wave, 4 KB            160 / 179 / 210 / 233
-//   weights        1-wave, 8 KB            176 / 189 / 208 / 220
+//   fused, 16-bit  1-wave, 2 KB            153 / 180 / 206 / 228   (16 bytes stored per lane,
+//   truncated      1-wave, 8 KB            151 / 173 / 201 / 222    see store_half_chunk_pair;
+//   weights        1-wave, 10 KB           154 / 172 / 198 / 219    8 bytes per lane: 160 / 180 /
+//                  1-wave, 12 KB           157 / 174 / 198 / 222    206 / 220 at the best cap)
 //   pack + unpack  1-wave, 8 / 10 / 12 KB  194 / 217 / 244 / 259 (best of the three)
 //   pack           1-wave, 4 KB            110 / 127 / 151 / 171   (4-wave: 112 / 129 / 152 / 175)
 //   unpack         1-wave, 6 KB            111 / 129 / 155 / 170   (no cap: 129 / 145 / 166 / 180;
@@ -60,7 +61,8 @@ struct LaunchShape {
     uint32_t extra_lds;   // bytes of dynamic LDS nothing touches
 };
 // written_per_weight: stream bytes plus the bytes of a truncated weight (4, 2 or 0)
-inline LaunchShape fused_shape(double written_per_weight) {
+inline LaunchShape fused_shape(double written_per_weight, bool out16) {
+    if (out16) return LaunchShape{1, written_per_weight <= 3.5 ? 8192u : 10240u};
     return LaunchShape{1, written_per_weight <= 4.5   ? 4096u
                           : written_per_weight <= 5.5 ? 6144u
                           : written_per_weight <= 6.5 ? 8192u
@@ -70,7 +72,11 @@ inline LaunchShape pack_unpack_shape(double bytes_per_weight) {
     return LaunchShape{1, bytes_per_weight <= 1.5 ? 8192u : bytes_per_weight <= 2.6 ? 10240u : 12288u};
 }
 inline LaunchShape pack_shape(double) { return LaunchShape{1, 4096u}; }
-inline LaunchShape unpack_shape(double) { return LaunchShape{kUnpackWaves, 6144u}; }
+// unpack to 16 bits reads about as much as it writes and wants more waves (2 KB:
+// 68 / 85 / 110 / 127 us; 6 KB: 83 / 97 / 117 / 133 us)
+inline LaunchShape unpack_shape(double, bool out16) {
+    return LaunchShape{kUnpackWaves, out16 ? 2048u : 6144u};
+}
 // Statistics: 4-wave blocks of 8192 weights, 16 waves per compute unit (78 us for 138 M weights,
 // 79 us uncapped, 81 - 85 us with 12 or fewer waves).
 inline LaunchShape stats_shape() { return LaunchShape{4, 36864u}; }

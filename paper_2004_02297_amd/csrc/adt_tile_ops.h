@@ -286,6 +286,53 @@ __device__ __forceinline__ void store_unpacked(void *dst, int e0, int len, const
     }
 }
 
+// 16-bit output of a full wave tile whose first element lies on the 16-byte
+// grid, two chunks (2p and 2p + 1) at a time.  A lane's four words of a chunk
+// make only 8 bytes, so neighbouring lanes trade halves (one DPP swap per
+// dword): the even lane stores 16 bytes of chunk 2p, the odd lane 16 bytes of
+// chunk 2p + 1.  The bytes written are those of store_unpacked per chunk.
+__device__ __forceinline__ uint32_t swap_with_neighbour_lane(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1 /* quad_perm [1,0,3,2] */, 0xF,
+                                                 0xF, false);
+}
+
+template <int OUT>
+__device__ __forceinline__ void store_half_chunk_pair(uint16_t *dst, int p, int lane,
+                                                      const u32x4 ua, const u32x4 ub) {
+    const bool odd = (lane & 1) != 0;
+    const uint32_t a0 = to_half_bits<OUT>(ua.x) | (to_half_bits<OUT>(ua.y) << 16);
+    const uint32_t a1 = to_half_bits<OUT>(ua.z) | (to_half_bits<OUT>(ua.w) << 16);
+    const uint32_t b0 = to_half_bits<OUT>(ub.x) | (to_half_bits<OUT>(ub.y) << 16);
+    const uint32_t b1 = to_half_bits<OUT>(ub.z) | (to_half_bits<OUT>(ub.w) << 16);
+    const uint32_t g0 = swap_with_neighbour_lane(odd ? a0 : b0);
+    const uint32_t g1 = swap_with_neighbour_lane(odd ? a1 : b1);
+    u32x4 o;
+    o.x = odd ? g0 : a0;
+    o.y = odd ? g1 : a1;
+    o.z = odd ? b0 : g0;
+    o.w = odd ? b1 : g1;
+    const int e0 = 4 * ((2 * p + (odd ? 1 : 0)) * kWave + (lane & ~1));
+    __builtin_nontemporal_store(o, (u32x4 *)(dst + e0));
+}
+
+// The unpacked words u[j] (chunk j) of a wave tile -> dst, in either format.
+template <int OUT>
+__device__ __forceinline__ void store_unpacked_tile(void *dst, int len, int lane,
+                                                    const u32x4 (&u)[kChunksPerLane]) {
+    if (OUT != kOutFp32 && len == kWaveTile && ((uintptr_t)dst & 15u) == 0) {   // wave uniform
+#pragma unroll
+        for (int p = 0; p < kChunksPerLane / 2; ++p)
+            store_half_chunk_pair<OUT>((uint16_t *)dst, p, lane, u[2 * p], u[2 * p + 1]);
+        return;
+    }
+    const bool dst_dw = ((uintptr_t)dst & 3u) == 0;        // wave uniform
+#pragma unroll
+    for (int j = 0; j < kChunksPerLane; ++j) {
+        const int e0 = 4 * (j * kWave + lane);
+        if (e0 < len) store_unpacked<OUT>(dst, e0, len, u[j], dst_dw);
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Unpack one wave tile: len*R stream bytes at src -> `len` FP32 words at dst.
 // [buf_lo, buf_hi) is the whole packed buffer: a 16-byte piece inside it may
@@ -299,7 +346,6 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
                                                  int lane) {
     const uint32_t s = (uint32_t)((uintptr_t)src & 15u);   // wave uniform
     const bool full = (len == kWaveTile);
-    const bool dst_dw = ((uintptr_t)dst & 3u) == 0;        // wave uniform
 
     if (full && s == 0) {
         constexpr int kPieces = R * kChunksPerLane / 4;     // 16-byte pieces per lane
@@ -310,14 +356,16 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
 #pragma unroll
         for (int k = 0; k < kPieces; ++k) *(u32x4 *)(lds + 4 * (k * kWave + lane)) = v[k];
         wave_lds_sync();
+        u32x4 u[kChunksPerLane];
 #pragma unroll
         for (int j = 0; j < kChunksPerLane; ++j) {
             const int c = j * kWave + lane;
             uint32_t y[4];
 #pragma unroll
             for (int t = 0; t < R; ++t) y[t] = lds[c * R + t];
-            store_unpacked<OUT>(dst, 4 * c, len, shift_to_top<R>(y), dst_dw);
+            u[j] = shift_to_top<R>(y);
         }
+        store_unpacked_tile<OUT>(dst, len, lane, u);
         return;
     }
 
@@ -345,11 +393,12 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
 
     // Stream byte b of the tile sits at LDS byte b + s.
     const uint32_t sh = s & 3u;
+    u32x4 u[kChunksPerLane];
 #pragma unroll
     for (int j = 0; j < kChunksPerLane; ++j) {
         const int c = j * kWave + lane;
-        const int e0 = 4 * c;
-        if (e0 < len) {
+        u[j] = u32x4{0u, 0u, 0u, 0u};
+        if (4 * c < len) {
             const int d = (int)(s + 4 * c * R) >> 2;        // <= kWaveTile - 1
             uint32_t x[5];
 #pragma unroll
@@ -357,9 +406,10 @@ __device__ __forceinline__ void unpack_wave_tile(const uint8_t *__restrict__ src
             uint32_t y[4];
 #pragma unroll
             for (int t = 0; t < R; ++t) y[t] = funnel(x[t + 1], x[t], sh);
-            store_unpacked<OUT>(dst, e0, len, shift_to_top<R>(y), dst_dw);
+            u[j] = shift_to_top<R>(y);
         }
     }
+    store_unpacked_tile<OUT>(dst, len, lane, u);
 }
 
 // ---------------------------------------------------------------------------

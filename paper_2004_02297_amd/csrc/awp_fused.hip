@@ -39,12 +39,10 @@ template <int R, int OUT>
 __device__ __forceinline__ void store_truncated(const u32x4 (&v)[kChunksPerLane],
                                                 void *__restrict__ dst, int len, int lane) {
     const uint32_t mask = R == 4 ? 0xFFFFFFFFu : (0xFFFFFFFFu << (8 * (4 - R)));
-    const bool dst_dw = ((uintptr_t)dst & 3u) == 0;       // wave uniform
+    u32x4 u[kChunksPerLane];
 #pragma unroll
-    for (int j = 0; j < kChunksPerLane; ++j) {
-        const int e0 = 4 * (j * kWave + lane);
-        if (e0 < len) store_unpacked<OUT>(dst, e0, len, v[j] & mask, dst_dw);
-    }
+    for (int j = 0; j < kChunksPerLane; ++j) u[j] = v[j] & mask;
+    store_unpacked_tile<OUT>(dst, len, lane, u);
 }
 
 // One wave tile: load once, then statistics (this lane's share of the tile's

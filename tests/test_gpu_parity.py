@@ -407,7 +407,7 @@ def test_ablation_variants_give_the_same_bytes(adt, variant):
 
 # ------------------------------------------------------------------ 16-bit unpack
 @pytest.mark.parametrize("fmt", ["bf16", "fp16"])
-@pytest.mark.parametrize("elem_shift,p_shift", [(0, 0), (1, 3)])
+@pytest.mark.parametrize("elem_shift,p_shift", [(0, 0), (1, 3), (4, 16), (8, 5)])
 def test_unpack16_ragged(adt, fmt, elem_shift, p_shift):
     off, rb, w = workloads.alignment_sweep_case()
     w = w.copy()

@@ -119,6 +119,51 @@ def test_plan_with_16_bit_truncated_weights(adt, out_dtype):
     assert n >= 2
 
 
+@pytest.mark.parametrize("out_dtype", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("shift", [0, 1, 2, 4, 8])
+def test_plan_16_bit_output_on_and_off_the_16_byte_grid(adt, out_dtype, shift):
+    """A full wave tile of 16-bit words that starts on the 16-byte grid is stored
+    16 bytes per lane (neighbouring lanes trade halves of two chunks), any other
+    tile 8 bytes or less per lane.  Layer sizes that are multiples of 8 put every
+    tile on the grid at shifts 0 and 8 and off it at 1, 2 and 4; every byte count
+    and the special values (NaNs, infinities, subnormals) take both routes."""
+    sizes = [8192, 1024, 6144, 8, 3072, 1000, 2048, 4096 + 16, 5120]
+    off = workloads.offsets_from_sizes(sizes)
+    L, N = len(sizes), int(off[-1])
+    rb = (np.arange(L) % 4 + 1).astype(np.uint8)
+    hw = workloads.random_bit_patterns(N, seed=77 + shift)
+    sp = workloads.special_values()
+    for l in range(L):                          # special values at the head and inside each layer
+        n = min(sp.size, sizes[l])
+        hw[off[l]:off[l] + n] = sp[:n]
+        if sizes[l] > 1024 + sp.size:
+            hw[off[l] + 1024:off[l] + 1024 + sp.size] = sp
+    w = torch.from_numpy(hw).cuda()
+    packed = torch.empty(4 * N, dtype=torch.uint8, device="cuda")
+    guard = 64
+    obuf = torch.zeros(N + shift + 2 * guard, dtype=out_dtype, device="cuda")
+    obuf.view(torch.int16).fill_(0x5A5A)
+    out = obuf[guard + shift:guard + shift + N]
+    plan = adt.AwpPlan(off, -1.0, 1000, 8, init_bits=rb.astype(np.int32) * 8)
+    plan.step(w, packed, out)
+    got = plan.read()
+    assert np.array_equal(got["bytes"], rb)
+    exp = oracle.pack(hw, off, rb)
+    assert np.array_equal(packed[:exp.size].cpu().numpy(), exp)
+    fmt = "bf16" if out_dtype == torch.bfloat16 else "fp16"
+    all16 = obuf.view(torch.int16).cpu().numpy().view(np.uint16)
+    lo, hi = guard + shift, guard + shift + N
+    assert np.all(all16[:lo] == 0x5A5A) and np.all(all16[hi:] == 0x5A5A)
+    assert np.array_equal(all16[lo:hi], oracle.unpack16(exp, off, rb, fmt))
+    # the separate 16-bit unpack takes the same two routes
+    obuf.view(torch.int16).fill_(0x5A5A)
+    adt.adt_unpack16(packed[:exp.size], off, rb, fmt, out=out)
+    all16 = obuf.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.all(all16[:lo] == 0x5A5A) and np.all(all16[hi:] == 0x5A5A)
+    assert np.array_equal(all16[lo:hi], oracle.unpack16(exp, off, rb, fmt))
+    plan.close()
+
+
 def test_plan_many_layers(adt):
     rng = np.random.default_rng(9)
     sizes = rng.integers(0, 3000, size=2500).tolist()     # rule kernel loops over 1024-layer chunks
