@@ -353,7 +353,7 @@ int pack_or_unpack(Direction dir, const void *weights, const int64_t *off,
     const bool unpack_dir = dir == kUnpack || dir == kUnpackBf16 || dir == kUnpackFp16;
     const double bpw = (double)p / (double)n;            // stream bytes per weight
     const LaunchShape shape =
-        dir == kPack ? shape_of(adt::kKernelPack, adt::pack_shape(bpw))
+        dir == kPack ? shape_of(adt::kKernelPack, adt::pack_shape(bpw, p > a.stream_cache_limit))
         : dir == kPackUnpack ? shape_of(adt::kKernelPackUnpack, adt::pack_unpack_shape(bpw))
                              : shape_of(adt::kKernelUnpack, adt::unpack_shape(bpw, dir != kUnpack));
     rc = build_tile_off(off, n_layers,
@@ -828,8 +828,8 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
     if (plan->n_tiles > 0) {
         const double out_bytes = out_format == adt::kOutFp32 ? 4.0 : out_format < 0 ? 0.0 : 2.0;
         const LaunchShape shape =
-            shape_of(adt::kKernelFused, adt::fused_shape(plan->bytes_per_weight_hint + out_bytes,
-                                                         out_bytes == 2.0));
+            shape_of(adt::kKernelFused,
+                     adt::fused_shape(plan->bytes_per_weight_hint + out_bytes, (int)out_bytes));
         e = adt::launch_fused(a, out_format, shape.waves, shape.extra_lds, hs);
         if (e != hipSuccess) return fail_hip(e, "fused launch");
     }

@@ -33,7 +33,7 @@ constexpr int kStatsTile = kBlock * kStatsLoadsPerLane * 4;
 // far fewer waves in flight than a compute unit could hold (32): measured on
 // 138 M weights with rotating output buffers (so that the last-level cache
 // cannot absorb rewrites), the kernels that write more than they read are
-// fastest with 9 to 13 waves per compute unit and lose 5 to 10 % at 32.  Two
+// fastest with 7 to 13 waves per compute unit and lose 5 to 10 % at 32.  Two
 // things make such a low occupancy work: blocks of ONE wavefront, so that a
 // compute unit is refilled the moment any wave retires (a four-wave block holds
 // the slots of its finished waves until the last one drains), and a wave that
@@ -41,19 +41,32 @@ constexpr int kStatsTile = kBlock * kStatsLoadsPerLane * 4;
 // table look-ups are scalar loads, see table_load).  The launchers request
 // dynamic LDS that no kernel touches; a compute unit has 160 KB, a one-wave
 // block of the pack / unpack kernels owns 4160 B of its own:
-//   extra 4 KB -> 19 waves, 6 KB -> 15, 8 KB -> 13, 10 KB -> 11, 12 KB -> 9.
-// Microseconds per launch, 138 M weights, all layers at 1 / 2 / 3 / 4 bytes:
-//   fused (plan)   4-wave blocks, no cap   223 / 250 / 283 / 298
-//                  1-wave, 8 KB            199 / 220 / 255 / 273
-//                  1-wave, 10 KB           211 / 224 / 248 / 263
-//   fused, 16-bit  1-wave, 2 KB            153 / 180 / 206 / 228   (16 bytes stored per lane,
-//   truncated      1-wave, 8 KB            151 / 173 / 201 / 222    see store_half_chunk_pair;
-//   weights        1-wave, 10 KB           154 / 172 / 198 / 219    8 bytes per lane: 160 / 180 /
-//                  1-wave, 12 KB           157 / 174 / 198 / 222    206 / 220 at the best cap)
-//   pack + unpack  1-wave, 8 / 10 / 12 KB  194 / 217 / 244 / 259 (best of the three)
-//   pack           1-wave, 4 KB            110 / 127 / 151 / 171   (4-wave: 112 / 129 / 152 / 175)
-//   unpack         1-wave, 6 KB            111 / 129 / 155 / 170   (no cap: 129 / 145 / 166 / 180;
-//                  right behind pack:      116 / 116 / 155 / 169    no cap: 126 / 119 / 164 / 178)
+//   extra 4 KB -> 19 waves, 6 KB -> 15, 8 KB -> 13, 10 KB -> 11, 12 KB -> 9,
+//   14 KB -> 8, 16 KB -> 7.
+// Microseconds per launch, 138 M weights, all layers at 1 / 2 / 3 / 4 bytes
+// (one-wave blocks; streaming stores, see store_streaming16):
+//   fused (plan),  4-wave blocks, no cap   223 / 250 / 283 / 298  (before the streaming stores)
+//   FP32 truncated 8 KB                    196 / 219 / 249 / 269
+//   weights        12 KB                   191 / 213 / 243 / 265
+//                  14 KB                   200 / 218 / 239 / 261
+//                  16 KB                   222 / 237 / 252 / 268
+//   fused, 16-bit  6 KB                    148 / 173 / 200 / 219
+//   truncated      8 KB                    148 / 171 / 201 / 220
+//   weights        10 KB                   152 / 173 / 196 / 217
+//                  12 KB                   157 / 178 / 197 / 215
+//   pack + unpack  8 KB                    195 / 217 / 248 / 268
+//                  12 KB                   190 / 215 / 243 / 266
+//                  14 KB                   187 / 210 / 239 / 261
+//                  16 KB                   193 / 212 / 236 / 257
+//                  20 KB                   204 / 221 / 250 / 255
+//   pack           4 KB, ordinary stores   105 / 120 /  -  /  -   (4-wave blocks: 112 / 129)
+//                  4 KB, streaming stores  111 / 127 / 149 / 171
+//                  10 KB, streaming stores 113 / 132 / 148 / 166
+//   unpack         2 KB                    112 / 134 / 159 / 175  (no cap: 129 / 145 / 166 / 180)
+//                  6 KB                    114 / 129 / 154 / 169
+//                  12 KB                   136 / 132 / 151 / 166
+//   right behind   6 KB                    117 / 114 / 154 / 168
+//   pack           12 KB                   140 / 117 / 151 / 166
 // The cap is chosen from the bytes written per weight (how write-heavy the
 // launch is).
 struct LaunchShape {
@@ -61,21 +74,25 @@ struct LaunchShape {
     uint32_t extra_lds;   // bytes of dynamic LDS nothing touches
 };
 // written_per_weight: stream bytes plus the bytes of a truncated weight (4, 2 or 0)
-inline LaunchShape fused_shape(double written_per_weight, bool out16) {
-    if (out16) return LaunchShape{1, written_per_weight <= 3.5 ? 8192u : 10240u};
-    return LaunchShape{1, written_per_weight <= 4.5   ? 4096u
-                          : written_per_weight <= 5.5 ? 6144u
-                          : written_per_weight <= 6.5 ? 8192u
-                                                      : 10240u};
+inline LaunchShape fused_shape(double written_per_weight, int out_bytes) {
+    if (out_bytes == 2)
+        return LaunchShape{1, written_per_weight <= 4.5   ? 8192u
+                              : written_per_weight <= 5.5 ? 10240u
+                                                          : 12288u};
+    if (out_bytes == 4) return LaunchShape{1, written_per_weight <= 6.5 ? 12288u : 14336u};
+    return LaunchShape{1, 4096u};       // statistics and stream only
 }
 inline LaunchShape pack_unpack_shape(double bytes_per_weight) {
-    return LaunchShape{1, bytes_per_weight <= 1.5 ? 8192u : bytes_per_weight <= 2.6 ? 10240u : 12288u};
+    return LaunchShape{1, bytes_per_weight <= 2.6 ? 14336u : 16384u};
 }
-inline LaunchShape pack_shape(double) { return LaunchShape{1, 4096u}; }
+// streaming: the stream is larger than the size up to which pack keeps it in the cache
+inline LaunchShape pack_shape(double, bool streaming) {
+    return LaunchShape{1, streaming ? 10240u : 4096u};
+}
 // unpack to 16 bits reads about as much as it writes and wants more waves (2 KB:
 // 68 / 85 / 110 / 127 us; 6 KB: 83 / 97 / 117 / 133 us)
-inline LaunchShape unpack_shape(double, bool out16) {
-    return LaunchShape{kUnpackWaves, out16 ? 2048u : 6144u};
+inline LaunchShape unpack_shape(double bytes_per_weight, bool out16) {
+    return LaunchShape{kUnpackWaves, out16 ? 2048u : bytes_per_weight <= 2.6 ? 6144u : 12288u};
 }
 // Statistics: 4-wave blocks of 8192 weights, 16 waves per compute unit (78 us for 138 M weights,
 // 79 us uncapped, 81 - 85 us with 12 or fewer waves).

@@ -33,6 +33,17 @@ typedef u32x4 u32x4_a4 __attribute__((aligned(4)));   // FP32 side: dword aligne
 //    them (a device-to-device copy of the stream placed there runs equally fast
 //    either way), and nontemporal stores are 2 - 5 % faster at every size
 //    (2 bytes: 218 vs 224 us, 4 bytes: 261 vs 274 us): always nontemporal.
+// A streaming store carries two cache-policy bits of the gfx940 family: `nt`
+// (nontemporal) and `sc1` (written through at device scope instead of staying
+// dirty in the L2 of the XCD).  With all of a wave's stores issued together at
+// its end, `sc1 nt` is 2 - 3 % faster than `nt` alone for the write-heavy
+// kernels (fused kernel at 2 bytes: 212 vs 217 us; `sc1` without `nt` is slower
+// than either).  The compiler sets `nt` for a nontemporal store and `sc1` for an
+// agent-scope atomic, but has no way to set both on a 128-bit store, so the
+// instruction is written out.  The gfx940 family needs two wait states before
+// a later VALU instruction may overwrite the data registers of a store wider
+// than 64 bits; the compiler keeps them for its own stores but does not look
+// into an asm statement, hence the s_nop 1 (= two wait states) behind the store.
 constexpr int64_t kPackStreamKeepInCacheBytes = (int64_t)320 << 20;
 constexpr int64_t kFusedStreamKeepInCacheBytes = 0;
 
@@ -49,8 +60,11 @@ __device__ __forceinline__ u32x4 load_fp32x4(const uint32_t *p) {
     if (ADT_NT_FP32_LOAD) return __builtin_nontemporal_load((const u32x4_a4 *)p);
     return *(const u32x4_a4 *)p;
 }
+__device__ __forceinline__ void store_streaming16(void *p, const u32x4 v) {   // p: 4-byte aligned
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+}
 __device__ __forceinline__ void store_fp32x4(uint32_t *p, const u32x4 v) {
-    if (ADT_NT_FP32_STORE) __builtin_nontemporal_store(v, (u32x4_a4 *)p);
+    if (ADT_NT_FP32_STORE) store_streaming16(p, v);
     else *(u32x4_a4 *)p = v;
 }
 __device__ __forceinline__ u32x4 load_stream16(const uint8_t *p) {   // 16-byte aligned
@@ -59,12 +73,7 @@ __device__ __forceinline__ u32x4 load_stream16(const uint8_t *p) {   // 16-byte 
 }
 __device__ __forceinline__ void store_stream16(uint8_t *p, const u32x4 v, bool nt) {
     if (nt) {                                   // nt is wave uniform
-        // The empty statements keep the two stores apart: without them the
-        // optimizer hoists / sinks both branches into one ordinary store and
-        // the hint is lost.
-        asm volatile("");
-        __builtin_nontemporal_store(v, (u32x4 *)p);
-        asm volatile("");
+        store_streaming16(p, v);
     } else {
         *(u32x4 *)p = v;
     }
@@ -312,7 +321,7 @@ __device__ __forceinline__ void store_half_chunk_pair(uint16_t *dst, int p, int 
     o.z = odd ? b0 : g0;
     o.w = odd ? b1 : g1;
     const int e0 = 4 * ((2 * p + (odd ? 1 : 0)) * kWave + (lane & ~1));
-    __builtin_nontemporal_store(o, (u32x4 *)(dst + e0));
+    store_streaming16(dst + e0, o);
 }
 
 // The unpacked words u[j] (chunk j) of a wave tile -> dst, in either format.

@@ -67,8 +67,10 @@ __device__ __forceinline__ void fused_wave_tile(const uint32_t *__restrict__ src
         }
         sum = (a0 + a1) + (a2 + a3);
     }
-    if (OUT != kOutNone) store_truncated<R, OUT>(v, wout, len, lane);
+    // all stores of the wave in one burst at its end (2 bytes: 217 us; truncated
+    // words first and the stream after the LDS pass: 220 us)
     stream_out_wave_tile<R>(v, stream, len, lds, lane, stream_nt);
+    if (OUT != kOutNone) store_truncated<R, OUT>(v, wout, len, lane);
 }
 
 // The layer a block tile belongs to, and where the tile starts in it.
