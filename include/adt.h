@@ -206,7 +206,10 @@ int awp_update(const double *l2_now, double *l2_prev, int32_t *counter,
  * Calls on one plan must be issued from one thread at a time and on one stream
  * (or on streams ordered by the caller).  The step allocates nothing and does
  * not wait for the GPU, so it may be captured into a HIP graph and replayed:
- * all state that changes from batch to batch lives on the device.
+ * all state that changes from batch to batch lives on the device.  (An eager
+ * step leaves the redo launch out while the host can tell, from a status word
+ * the device publishes, that no interval counter can reach INTERVAL in this
+ * batch; a captured step always contains it.)
  * awp_plan_read waits for the steps enqueued so far and copies the state to
  * host arrays (any pointer may be NULL): stats n_layers*AWP_NSTATS doubles,
  * bits / counter / bytes n_layers entries, packed_size one value.

@@ -34,14 +34,21 @@ def lib_path() -> str:
     return _build.LIB
 
 
+_DIGEST_MARKER = b"adt-source-digest:"
+
+
 def _built_digest(path: str):
-    """adt_source_digest() of the library file at `path` (None: not exported)."""
-    lib = ctypes.CDLL(path)
-    if not hasattr(lib, "adt_source_digest"):
-        return None, lib
-    lib.adt_source_digest.restype = ctypes.c_char_p
-    lib.adt_source_digest.argtypes = []
-    return lib.adt_source_digest().decode(), lib
+    """Source digest a built library file carries, read from the file's bytes:
+    the file is not mapped, because a library that has been mapped once stays
+    mapped under its path and a rebuilt file would not replace it.  None: the
+    file carries no digest."""
+    with open(path, "rb") as f:
+        data = f.read()
+    at = data.find(_DIGEST_MARKER)
+    if at < 0:
+        return None
+    start = at + len(_DIGEST_MARKER)
+    return data[start:data.index(b"\0", start)].decode()
 
 
 def load_library():
@@ -53,17 +60,21 @@ def load_library():
         return _lib
     if not os.path.exists(_build.LIB):
         _build.build_library()
-    digest, lib = _built_digest(_build.LIB)
     want = _build.source_digest()
-    if digest != want:
-        del lib
-        # os.replace gives the rebuilt file a new inode, so the second dlopen maps the new code
+    if _built_digest(_build.LIB) != want:
         _build.build_library()
-        digest, lib = _built_digest(_build.LIB)
+        digest = _built_digest(_build.LIB)
         if digest != want:
             raise RuntimeError("libadt.so at %s was built from other sources (digest %r, the "
                                "tree has %r) and rebuilding did not change that"
                                % (_build.LIB, digest, want))
+    lib = ctypes.CDLL(_build.LIB)
+    lib.adt_source_digest.restype = ctypes.c_char_p
+    lib.adt_source_digest.argtypes = []
+    if lib.adt_source_digest().decode() != want:
+        raise RuntimeError("libadt.so at %s reports digest %r after loading, the tree has %r: another "
+                           "build of it is already mapped in this process"
+                           % (_build.LIB, lib.adt_source_digest().decode(), want))
     P, I, I64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
     lib.adt_packed_size.restype = I64
     lib.adt_packed_size.argtypes = [P, P, I]

@@ -59,6 +59,14 @@ struct awp_plan {
     uint32_t *tile_off = nullptr, *partial_absmax = nullptr;
     uint8_t *rbytes = nullptr;
     int32_t *bits = nullptr, *counter = nullptr, *changed = nullptr, *steps_done = nullptr;
+    // Leaving the redo launch out (see plan_step): what the fused kernel's first
+    // thread keeps on the device, the pinned host word it publishes, and the
+    // host's own count of the batches issued since creation / set_state.
+    int32_t *rule_seen = nullptr, *max_counter = nullptr;
+    uint32_t *batch_count = nullptr;
+    unsigned long long *host_status = nullptr;
+    uint32_t issued = 0;
+    bool captured = false;      // a step went into a graph: replays are not counted, always redo
     double *l2_prev = nullptr, *stats = nullptr, *partial_sumsq = nullptr;
     // final + rule kernel: its sub-blocks (see adt::FinalSub)
     int n_subs = 0;
@@ -718,6 +726,7 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     const size_t o_tile = take(4 * L1), o_pmax = take(4 * n_partials);
     const size_t o_bits = take(4 * G), o_cnt = take(4 * G), o_grp = take(4 * (G + 1));
     const size_t o_chg = take(4), o_steps = take(4), o_rb = take(L);
+    const size_t o_seen = take(4), o_maxc = take(4), o_batch = take(4);
     const size_t o_subs = take(sizeof(adt::FinalSub) * S), o_ssum = take(8 * S), o_smax = take(4 * S);
     const size_t o_lso = take(4 * L1), o_gsubs = take(4 * G), o_gtick = take(4 * G);
     const size_t total = o + 8;
@@ -737,6 +746,9 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     pl->group_off = (int32_t *)(b + o_grp);
     pl->changed = (int32_t *)(b + o_chg);
     pl->steps_done = (int32_t *)(b + o_steps);
+    pl->rule_seen = (int32_t *)(b + o_seen);
+    pl->max_counter = (int32_t *)(b + o_maxc);
+    pl->batch_count = (uint32_t *)(b + o_batch);
     pl->rbytes = (uint8_t *)(b + o_rb);
     pl->subs = (adt::FinalSub *)(b + o_subs);
     pl->sub_sumsq = (double *)(b + o_ssum);
@@ -745,6 +757,16 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     pl->group_subs = (int32_t *)(b + o_gsubs);
     pl->group_ticket = (int32_t *)(b + o_gtick);
 
+    // The status word is a convenience: without it every step launches the redo pass.
+    if (pl->n_tiles > 0 && n_groups <= adt::kStatusMaxGroups) {
+        void *hp = nullptr;
+        if (hipHostMalloc(&hp, 8, hipHostMallocDefault) == hipSuccess) {
+            pl->host_status = (unsigned long long *)hp;
+            *pl->host_status = 0;       // no batch begun, largest counter 0
+        } else {
+            (void)hipGetLastError();
+        }
+    }
     e = hipMemset(b, 0, total);
     if (e == hipSuccess) e = hipMemcpy(pl->elem_off, layer_offsets, 8 * L1, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(pl->pack_off, pack_off.data(), 8 * L1, hipMemcpyHostToDevice);
@@ -763,6 +785,7 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         (void)hipFree(pl->block);
+        if (pl->host_status) (void)hipHostFree(pl->host_status);
         delete pl;
         return fail_hip(e, "plan upload");
     }
@@ -821,6 +844,11 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
     a.partial_sumsq = plan->partial_sumsq;
     a.partial_absmax = plan->partial_absmax;
     a.changed = plan->changed;
+    a.steps_done = plan->steps_done;
+    a.rule_seen = plan->rule_seen;
+    a.batch_count = plan->batch_count;
+    a.max_counter = plan->max_counter;
+    a.host_status = plan->host_status;
     a.stream_cache_limit = g_fused_cache_limit.load();
     a.n_layers = plan->n_layers;
     a.n_tiles = plan->n_tiles;
@@ -851,7 +879,10 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
     r.counter = plan->counter;
     r.rbytes = plan->rbytes;
     r.changed = plan->changed;
-    r.steps_done = plan->steps_done;
+    // with tiles the fused kernel's first thread has set steps_done for this batch
+    // already and left the previous value in rule_seen
+    r.steps_done = plan->n_tiles > 0 ? plan->rule_seen : plan->steps_done;
+    r.max_counter = plan->host_status ? plan->max_counter : nullptr;
     r.T = plan->T;
     r.interval = plan->interval;
     r.n_bits = plan->n_bits;
@@ -860,8 +891,30 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
         if (e != hipSuccess) return fail_hip(e, "final + rule launch");
     }
     ++plan->steps;
-    e = adt::launch_redo(a, out_format, plan->pack_off, plan->packed_size, plan->steps_done, hs);
-    if (e != hipSuccess) return fail_hip(e, "redo launch");
+    // The redo pass has something to do only in a batch that takes a group's
+    // counter to INTERVAL.  The status word says how large the largest counter
+    // was after some earlier batch; every batch issued since adds at most one.
+    // If even that bound stays below INTERVAL - 1 before this batch, no byte
+    // count can move and the launch is left out.  A stale or never-updated word
+    // only makes the bound larger.  Under graph capture the decision would be
+    // frozen into the graph and replays are not counted here: always launch.
+    bool redo = true;
+    if (plan->host_status && !plan->captured) {
+        if (stream_is_capturing(hs)) {
+            plan->captured = true;
+        } else {
+            const unsigned long long word =
+                __atomic_load_n(plan->host_status, __ATOMIC_RELAXED);
+            const uint32_t begun = (uint32_t)(word >> 32), top = (uint32_t)word;
+            const uint64_t bound = (uint64_t)top + (uint32_t)(plan->issued - begun);
+            redo = bound + 1 >= (uint64_t)plan->interval;
+        }
+    }
+    ++plan->issued;
+    if (redo) {
+        e = adt::launch_redo(a, out_format, plan->pack_off, plan->packed_size, plan->steps_done, hs);
+        if (e != hipSuccess) return fail_hip(e, "redo launch");
+    }
     return ADT_OK;
 }
 }  // namespace
@@ -938,7 +991,16 @@ int awp_plan_set_state(awp_plan *plan, const int32_t *bits, const int32_t *count
     put(plan->pack_off, pack_off.data(), 8 * (L + 1));
     put(plan->packed_size, &p, 8);
     put(plan->steps_done, &seen, 4);
+    int32_t top = 0;                            // the counting of batches starts over
+    for (size_t g = 0; g < G; ++g) top = counter[g] > top ? counter[g] : top;
+    const uint32_t zero = 0;
+    put(plan->max_counter, &top, 4);
+    put(plan->batch_count, &zero, 4);
     if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e == hipSuccess && plan->host_status) {
+        __atomic_store_n(plan->host_status, (unsigned long long)(uint32_t)top, __ATOMIC_RELAXED);
+        plan->issued = 0;
+    }
     if (e != hipSuccess) return fail_hip(e, "plan set_state");
     if (plan->n > 0) plan->bytes_per_weight_hint = (double)p / (double)plan->n;
     return ADT_OK;
@@ -949,7 +1011,10 @@ int awp_plan_destroy(awp_plan *plan) {
     if (plan->block) {
         int saved = 0;
         const bool have = hipGetDevice(&saved) == hipSuccess;
-        if (hipSetDevice(plan->device) == hipSuccess) (void)hipFree(plan->block);   // waits
+        if (hipSetDevice(plan->device) == hipSuccess) {
+            (void)hipFree(plan->block);   // waits
+            if (plan->host_status) (void)hipHostFree(plan->host_status);
+        }
         if (have) (void)hipSetDevice(saved);
     }
     delete plan;
@@ -1053,7 +1118,10 @@ const char *adt_last_error(void) { return g_err.c_str(); }
 #ifndef ADT_SOURCE_DIGEST
 #define ADT_SOURCE_DIGEST ""
 #endif
-const char *adt_source_digest(void) { return ADT_SOURCE_DIGEST; }
+// The marker lets a loader find the digest in the file's bytes without mapping
+// the library (a library once mapped stays mapped under its path).
+static const char kSourceDigest[] = "adt-source-digest:" ADT_SOURCE_DIGEST;
+const char *adt_source_digest(void) { return kSourceDigest + sizeof("adt-source-digest:") - 1; }
 
 int64_t adt_stream_cache_limit(int kernel, int64_t bytes) {
     std::atomic<int64_t> *limit = kernel == adt::kKernelPack ? &g_pack_cache_limit

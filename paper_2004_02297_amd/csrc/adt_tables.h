@@ -204,6 +204,13 @@ struct FusedArgs {
     double *partial_sumsq;      // one per wave tile: 4 * n_tiles entries
     uint32_t *partial_absmax;
     int32_t *changed;           // cleared by the fused kernel, raised by the rule, read by redo
+    // Bookkeeping of a batch, done by the fused kernel's first thread before
+    // anything of the batch is reduced (see begin_batch in awp_fused.hip):
+    int32_t *steps_done;        // non-zero once a batch has been processed
+    int32_t *rule_seen;         // steps_done as it was before this batch: what the rule reads
+    uint32_t *batch_count;      // batches begun since the plan was created or its state set
+    int32_t *max_counter;       // largest interval counter the rule left behind (previous batch)
+    unsigned long long *host_status;   // pinned host word (batches << 32 | max counter); may be null
     int64_t stream_cache_limit;   // streams larger than this are written nontemporal
     int n_layers;
     uint32_t n_tiles;
@@ -239,6 +246,7 @@ struct FinalRuleArgs {
     uint8_t *rbytes;            // per layer
     int32_t *changed;
     const int32_t *steps_done;  // 0 before the first batch: that batch only records norms
+    int32_t *max_counter;       // raised to every group's counter after the rule; null: not kept
     double T;
     int interval;
     int n_bits;
@@ -248,5 +256,8 @@ struct FinalRuleArgs {
 // Redo pass: layers whose stream-offset table fits the kernel's LDS, and its grid.
 constexpr int kRedoLdsLayers = 1024;
 constexpr int kRedoBlocks = 1024;
+// Plans with more groups than this do not keep the largest interval counter
+// (one atomic per group and batch) and launch the redo pass with every batch.
+constexpr int kStatusMaxGroups = 4096;
 
 }  // namespace adt

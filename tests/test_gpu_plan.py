@@ -448,6 +448,100 @@ def test_launch_timing_stays_out_of_a_captured_graph(adt):
     plan.close()
 
 
+def count_redo_launches(adt, fn):
+    """Run fn() with launch timing on; returns {kernel name: launches}."""
+    adt.adt_timing_enable(True, 4096)
+    adt.adt_timing_read()
+    fn()
+    torch.cuda.synchronize()
+    t = adt.adt_timing_read()
+    adt.adt_timing_enable(False)
+    return {k: v["launches"] for k, v in t.items()}
+
+
+@pytest.mark.parametrize("sync_every_step", [True, False])
+def test_plan_leaves_the_redo_launch_out_only_when_nothing_can_change(adt, sync_every_step):
+    """With INTERVAL = 6 and every batch counting, a layer's byte count moves on
+    batches 7, 13, 19, ... (the first batch only records norms).  The library may
+    leave the redo launch out while the host can prove, from the counter status
+    the device publishes, that no counter can reach INTERVAL; every step still has
+    to equal the oracle, with the host running ahead of the device or not."""
+    sizes = [5000, 4096, 1, 0, 9000, 12289]
+    off = workloads.offsets_from_sizes(sizes)
+    L, N = len(sizes), int(off[-1])
+    rng = np.random.default_rng(61)
+    hw = rng.standard_normal(N).astype(np.float32) * np.float32(0.05)
+    steps, interval = 40, 6
+    ws = [torch.from_numpy(hw * np.float32(0.99) ** i).cuda() for i in range(steps)]   # norms shrink
+    ps = [torch.full((4 * N,), 0xA5, dtype=torch.uint8, device="cuda") for _ in range(steps)]
+    outs = [torch.zeros(N, dtype=torch.float32, device="cuda") for _ in range(steps)]
+    plan = adt.AwpPlan(off, 0.0, interval, 8)
+
+    def run():
+        for i in range(steps):
+            plan.step(ws[i], ps[i], outs[i])
+            if sync_every_step:
+                torch.cuda.synchronize()
+
+    launches = count_redo_launches(adt, run)
+    assert launches["fused_kernel"] == steps and launches["final_rule_kernel"] == steps
+    ost = oracle.AwpState(L, 8)
+    changes, prev = 0, None
+    for i in range(steps):
+        hwi = ws[i].cpu().numpy()
+        orb = oracle.awp_update(ost, oracle.stats(hwi, off)[:, 1], 0.0, interval, 8)
+        exp = oracle.pack(hwi, off, orb)
+        assert np.array_equal(ps[i][:exp.size].cpu().numpy(), exp), i
+        assert np.array_equal(outs[i].view(torch.int32).cpu().numpy(),
+                              oracle.unpack(exp, off, orb).view(np.int32)), i
+        if prev is not None and not np.array_equal(prev, orb):
+            changes += 1
+        prev = orb
+    got = plan.read()
+    assert np.array_equal(got["bytes"], prev) and np.array_equal(got["counter"], ost.counter)
+    assert changes == 3                                  # 8 -> 16 -> 24 -> 32 bits
+    assert changes <= launches["redo_kernel"] <= steps
+    if sync_every_step:
+        # the host sees a fresh status word before every step: redo only where a counter stands at
+        # INTERVAL - 1 or, the word being one batch old, may stand there: two batches in six
+        assert launches["redo_kernel"] <= 14
+    plan.close()
+
+
+def test_plan_resumed_next_to_a_change_runs_the_redo_pass(adt):
+    """State restored with a counter one short of INTERVAL: the very next batch
+    changes the byte count, so the first step after set_state must not leave
+    the redo launch out."""
+    sizes = [6000, 4096, 3000]
+    off = workloads.offsets_from_sizes(sizes)
+    N = int(off[-1])
+    rng = np.random.default_rng(62)
+    hw = rng.standard_normal(N).astype(np.float32) * np.float32(0.05)
+    interval = 1000
+    plan = adt.AwpPlan(off, 0.0, interval, 8)
+    w = torch.from_numpy(hw).cuda()
+    packed = torch.zeros(4 * N, dtype=torch.uint8, device="cuda")
+    out = torch.zeros(N, dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        plan.step(w, packed, out)
+    norms = oracle.stats(hw, off)[:, 1]
+    plan.set_state({"bits": np.array([8, 16, 8], np.int32),
+                    "counter": np.array([interval - 1, 5, interval - 2], np.int32),
+                    "l2_prev": norms * 2.0, "batches_seen": 1})     # this batch's norms are smaller: counts
+    plan.step(w, packed, out)
+    got = plan.read()
+    assert got["bits"].tolist() == [16, 16, 8] and got["counter"].tolist() == [0, 6, interval - 1]
+    rb = np.array([2, 2, 1], np.uint8)
+    exp = oracle.pack(hw, off, rb)
+    assert got["packed_size"] == exp.size
+    assert np.array_equal(packed[:exp.size].cpu().numpy(), exp)
+    assert np.array_equal(out.view(torch.int32).cpu().numpy(), oracle.unpack(exp, off, rb).view(np.int32))
+    plan.step(w, packed, out)                # same weights again
+    got = plan.read()
+    assert got["counter"].tolist() == [0, 6, interval - 1]      # equal norms do not count with T = 0
+    plan.close()
+
+
 def test_plan_checkpoint_and_resume(adt):
     """A plan rebuilt from get_state() continues exactly like the original."""
     sizes = [3000, 4096, 17, 9000, 5000]

@@ -247,3 +247,39 @@ def test_stale_library_is_rebuilt(monkeypatch, adt):
     with pytest.raises(RuntimeError, match="built from other sources"):
         binding.load_library()
     assert calls == [1] and binding._lib is None
+
+
+def test_stale_file_is_replaced_before_anything_is_mapped(tmp_path):
+    """The stale check reads the digest from the file and maps the library only
+    once it is current: a process that finds a stale file ends up running the
+    rebuilt code (run in a child process, which has mapped nothing yet)."""
+    import subprocess
+    import sys
+    from paper_2004_02297_amd import _build
+    code = r"""
+import os, shutil, sys
+from paper_2004_02297_amd import _build, binding
+real = _build.LIB
+fake = os.path.join(sys.argv[1], "libadt.so")
+data = open(real, "rb").read()
+at = data.index(binding._DIGEST_MARKER) + len(binding._DIGEST_MARKER)
+open(fake, "wb").write(data[:at] + b"0" * 16 + data[at + 16:])      # same code, another digest
+assert binding._built_digest(fake) == "0" * 16
+calls = []
+def rebuild(verbose=False):
+    calls.append(1)
+    tmp = fake + ".new"
+    shutil.copyfile(real, tmp)
+    os.replace(tmp, fake)
+_build.LIB = fake
+_build.build_library = rebuild
+lib = binding.load_library()
+assert calls == [1]
+assert lib.adt_source_digest().decode() == _build.source_digest()
+print("ok")
+"""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-c", code, str(tmp_path)], cwd=root, capture_output=True,
+                         text=True, timeout=300)
+    assert out.returncode == 0 and out.stdout.strip().endswith("ok"), out.stderr[-2000:]
+    assert _build.source_digest()
