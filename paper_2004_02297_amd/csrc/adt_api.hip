@@ -62,7 +62,7 @@ struct awp_plan {
     // Leaving the redo launch out (see plan_step): what the fused kernel's first
     // thread keeps on the device, the pinned host word it publishes, and the
     // host's own count of the batches issued since creation / set_state.
-    int32_t *rule_seen = nullptr, *max_counter = nullptr;
+    int32_t *rule_seen = nullptr;
     uint32_t *batch_count = nullptr;
     unsigned long long *host_status = nullptr;
     uint32_t issued = 0;
@@ -726,7 +726,7 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     const size_t o_tile = take(4 * L1), o_pmax = take(4 * n_partials);
     const size_t o_bits = take(4 * G), o_cnt = take(4 * G), o_grp = take(4 * (G + 1));
     const size_t o_chg = take(4), o_steps = take(4), o_rb = take(L);
-    const size_t o_seen = take(4), o_maxc = take(4), o_batch = take(4);
+    const size_t o_seen = take(4), o_batch = take(4);
     const size_t o_subs = take(sizeof(adt::FinalSub) * S), o_ssum = take(8 * S), o_smax = take(4 * S);
     const size_t o_lso = take(4 * L1), o_gsubs = take(4 * G), o_gtick = take(4 * G);
     const size_t total = o + 8;
@@ -747,7 +747,6 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     pl->changed = (int32_t *)(b + o_chg);
     pl->steps_done = (int32_t *)(b + o_steps);
     pl->rule_seen = (int32_t *)(b + o_seen);
-    pl->max_counter = (int32_t *)(b + o_maxc);
     pl->batch_count = (uint32_t *)(b + o_batch);
     pl->rbytes = (uint8_t *)(b + o_rb);
     pl->subs = (adt::FinalSub *)(b + o_subs);
@@ -847,7 +846,8 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
     a.steps_done = plan->steps_done;
     a.rule_seen = plan->rule_seen;
     a.batch_count = plan->batch_count;
-    a.max_counter = plan->max_counter;
+    a.counter = plan->counter;
+    a.n_status_groups = plan->host_status ? plan->n_groups : 0;
     a.host_status = plan->host_status;
     a.stream_cache_limit = g_fused_cache_limit.load();
     a.n_layers = plan->n_layers;
@@ -882,7 +882,6 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
     // with tiles the fused kernel's first thread has set steps_done for this batch
     // already and left the previous value in rule_seen
     r.steps_done = plan->n_tiles > 0 ? plan->rule_seen : plan->steps_done;
-    r.max_counter = plan->host_status ? plan->max_counter : nullptr;
     r.T = plan->T;
     r.interval = plan->interval;
     r.n_bits = plan->n_bits;
@@ -994,7 +993,6 @@ int awp_plan_set_state(awp_plan *plan, const int32_t *bits, const int32_t *count
     int32_t top = 0;                            // the counting of batches starts over
     for (size_t g = 0; g < G; ++g) top = counter[g] > top ? counter[g] : top;
     const uint32_t zero = 0;
-    put(plan->max_counter, &top, 4);
     put(plan->batch_count, &zero, 4);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e == hipSuccess && plan->host_status) {

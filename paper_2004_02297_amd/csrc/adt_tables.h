@@ -209,8 +209,9 @@ struct FusedArgs {
     int32_t *steps_done;        // non-zero once a batch has been processed
     int32_t *rule_seen;         // steps_done as it was before this batch: what the rule reads
     uint32_t *batch_count;      // batches begun since the plan was created or its state set
-    int32_t *max_counter;       // largest interval counter the rule left behind (previous batch)
-    unsigned long long *host_status;   // pinned host word (batches << 32 | max counter); may be null
+    const int32_t *counter;     // per group: interval counters as the previous batch left them
+    int n_status_groups;        // number of groups if the status word is kept, else 0
+    unsigned long long *host_status;   // pinned host word (batches << 32 | largest counter); may be null
     int64_t stream_cache_limit;   // streams larger than this are written nontemporal
     int n_layers;
     uint32_t n_tiles;
@@ -246,7 +247,6 @@ struct FinalRuleArgs {
     uint8_t *rbytes;            // per layer
     int32_t *changed;
     const int32_t *steps_done;  // 0 before the first batch: that batch only records norms
-    int32_t *max_counter;       // raised to every group's counter after the rule; null: not kept
     double T;
     int interval;
     int n_bits;
@@ -256,8 +256,9 @@ struct FinalRuleArgs {
 // Redo pass: layers whose stream-offset table fits the kernel's LDS, and its grid.
 constexpr int kRedoLdsLayers = 1024;
 constexpr int kRedoBlocks = 1024;
-// Plans with more groups than this do not keep the largest interval counter
-// (one atomic per group and batch) and launch the redo pass with every batch.
+// Plans with more groups than this do not publish the largest interval counter
+// (one wavefront scans the counters at the start of every batch) and launch the
+// redo pass with every batch.
 constexpr int kStatusMaxGroups = 4096;
 
 }  // namespace adt

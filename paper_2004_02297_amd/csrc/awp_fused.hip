@@ -125,24 +125,30 @@ __device__ __forceinline__ void fused_block_wave_tile(const FusedArgs &a, const 
     }
 }
 
-// One thread, before anything of the batch is reduced: clears `changed`, hands
-// the rule the "has a batch been seen" flag as it was before this batch, and
-// publishes to the host how far the interval counters had got after the previous
-// batch.  A byte count can only move in a batch that takes some counter to
-// INTERVAL (Algorithm 1), and a counter grows by at most one per batch, so the
-// host can tell from an old status word that the next batches cannot change
-// anything and leave the redo launch out (see plan_step).
-__device__ __forceinline__ void begin_batch(const FusedArgs &a) {
+// The first wavefront, before anything of the batch is reduced: clears
+// `changed`, hands the rule the "has a batch been seen" flag as it was before
+// this batch, and publishes to the host how far the interval counters had got
+// after the previous batch.  A byte count can only move in a batch that takes
+// some counter to INTERVAL (Algorithm 1), and a counter grows by at most one
+// per batch, so the host can tell from an old status word that the next batches
+// cannot change anything and leave the redo launch out (see plan_step).  All
+// 64 lanes must be active.
+__device__ __forceinline__ void begin_batch(const FusedArgs &a, int lane) {
+    uint32_t top = 0u;
+    for (int g = lane; g < a.n_status_groups; g += kWave) {
+        const uint32_t c = (uint32_t)a.counter[g];
+        top = c > top ? c : top;
+    }
+    top = wave_max(top);
+    if (lane != 0) return;
     *a.changed = 0;                     // raised by the rule if need be
     *a.rule_seen = *a.steps_done;
     *a.steps_done = 1;
     const uint32_t begun = *a.batch_count;
     *a.batch_count = begun + 1u;
-    const int32_t top = *a.max_counter;
-    *a.max_counter = 0;
     if (a.host_status)
-        __hip_atomic_store(a.host_status, ((unsigned long long)begun << 32) | (uint32_t)top,
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_store(a.host_status, ((unsigned long long)begun << 32) | top, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // Speculative pass.  Wave tile number wt = 4 * (block tile) + k gets one
@@ -158,7 +164,7 @@ __global__ __launch_bounds__(WAVES * kWave) void fused_kernel(const FusedArgs a)
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
     const uint32_t wt = WAVES == 1 ? blockIdx.x : blockIdx.x * (uint32_t)kWavesPerBlock + (uint32_t)wave;
-    if (wt == 0 && lane == 0) begin_batch(a);
+    if (wt == 0) begin_batch(a, lane);        // wave uniform
     const BlockTileRef t = find_block_tile(a, wt / kWavesPerBlock);
     const bool nt = table_load(a.pack_off, a.n_layers) > a.stream_cache_limit;   // whole stream
     double sum = 0.0;
@@ -254,9 +260,6 @@ __global__ __launch_bounds__(kFinalBlock) void final_rule_kernel(const FinalRule
         a.counter[g] = counter;
         a.bits[g] = bits;
     }
-    if (a.max_counter)      // result unused: an atomic without return
-        (void)__hip_atomic_fetch_max(a.max_counter, counter, __ATOMIC_RELAXED,
-                                     __HIP_MEMORY_SCOPE_AGENT);
     a.l2_prev[g] = now;
     const int r = (bits + 7) >> 3;
     bool moved = false;
