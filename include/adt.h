@@ -227,6 +227,18 @@ int awp_adt_step16(awp_plan *plan, const float *weights, uint8_t *packed,
 int awp_plan_read(awp_plan *plan, double *stats, int32_t *bits, int32_t *counter,
                   uint8_t *bytes, int64_t *packed_size);
 /*
+ * While no byte count can move (see above), an eager step leaves the final
+ * reduction of its statistics and the rule to the next step, whose first kernel
+ * carries them along; the packed stream and the truncated weights are complete
+ * in stream order all the same.  awp_plan_flush enqueues that leftover work now,
+ * on the stream of the last step, without waiting (no-op if there is none), for
+ * a caller that wants the plan's state settled in stream order, e.g. before an
+ * event.  awp_plan_read, awp_plan_get_state and awp_plan_set_state do the same
+ * by themselves.  Capturing a step while such work is left over is refused with
+ * ADT_EINVAL: call one of these first.
+ */
+int awp_plan_flush(awp_plan *plan);
+/*
  * Checkpoint / resume of a plan's AWP state (host arrays, one entry per layer,
  * or per group for a grouped plan; any pointer may be NULL).  get waits for
  * the steps enqueued so far; set replaces the state, recomputes the byte counts

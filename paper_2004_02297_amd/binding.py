@@ -117,6 +117,8 @@ def load_library():
     lib.awp_adt_step16.argtypes = [P, P, P, I64, P, I, P]
     lib.awp_plan_read.restype = I
     lib.awp_plan_read.argtypes = [P, P, P, P, P, P]
+    lib.awp_plan_flush.restype = I
+    lib.awp_plan_flush.argtypes = [P]
     lib.awp_plan_get_state.restype = I
     lib.awp_plan_get_state.argtypes = [P, P, P, P, P]
     lib.awp_plan_set_state.restype = I
@@ -413,6 +415,10 @@ class AwpPlan:
         else:
             _check(self._lib.awp_adt_step(self._h, w.data_ptr() or None, p.data_ptr() or None,
                                           p.numel(), optr, _stream(stream)))
+
+    def flush(self) -> None:
+        """awp_plan_flush: enqueue what the last step left to the next one (no wait)."""
+        _check(self._lib.awp_plan_flush(self._h))
 
     def read(self) -> dict:
         """awp_plan_read: waits for the enqueued steps, returns the state."""

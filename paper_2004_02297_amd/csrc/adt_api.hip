@@ -62,15 +62,20 @@ struct awp_plan {
     // Leaving the redo launch out (see plan_step): what the fused kernel's first
     // thread keeps on the device, the pinned host word it publishes, and the
     // host's own count of the batches issued since creation / set_state.
-    int32_t *rule_seen = nullptr;
+    int32_t *rule_seen = nullptr;       // two entries, one per set of partials
     uint32_t *batch_count = nullptr;
     unsigned long long *host_status = nullptr;
     uint32_t issued = 0;
     bool captured = false;      // a step went into a graph: replays are not counted, always redo
+    // Two sets of statistics partials.  While no byte count can move, a batch's
+    // final reduction and rule are not launched behind its fused kernel but ride
+    // at the head of the next batch's fused kernel (or are launched by whoever
+    // needs the state first): `pending` says that set `pending_set` waits for that.
+    int cur_set = 0, pending_set = 0;
+    bool pending = false;
     double *l2_prev = nullptr, *stats = nullptr, *partial_sumsq = nullptr;
-    // final + rule kernel: its sub-blocks (see adt::FinalSub)
+    // final reduction + rule: its sub-blocks (see adt::FinalSub)
     int n_subs = 0;
-    std::vector<adt::FinalSub> host_subs;   // copy for the kernel arguments of small plans
     adt::FinalSub *subs = nullptr;
     uint32_t *layer_sub_off = nullptr, *sub_absmax = nullptr;
     int32_t *group_subs = nullptr, *group_ticket = nullptr;
@@ -715,18 +720,17 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     }
     const size_t S = subs.size();
     pl->n_subs = (int)S;
-    if (S <= (size_t)adt::kFinalInlineSubs) pl->host_subs = subs;
 
     // carve one allocation; 8-byte items first
     size_t o = 0;
     auto take = [&o](size_t bytes) { size_t at = o; o += align8(bytes); return at; };
     const size_t o_elem = take(8 * L1), o_pack = take(8 * L1), o_psize = take(8);
     const size_t n_partials = (size_t)pl->n_tiles * adt::kWavesPerBlock;   // one per wave tile
-    const size_t o_prev = take(8 * G), o_stats = take(24 * L), o_psum = take(8 * n_partials);
-    const size_t o_tile = take(4 * L1), o_pmax = take(4 * n_partials);
+    const size_t o_prev = take(8 * G), o_stats = take(24 * L), o_psum = take(2 * 8 * n_partials);
+    const size_t o_tile = take(4 * L1), o_pmax = take(2 * 4 * n_partials);
     const size_t o_bits = take(4 * G), o_cnt = take(4 * G), o_grp = take(4 * (G + 1));
     const size_t o_chg = take(4), o_steps = take(4), o_rb = take(L);
-    const size_t o_seen = take(4), o_batch = take(4);
+    const size_t o_seen = take(2 * 4), o_batch = take(4);
     const size_t o_subs = take(sizeof(adt::FinalSub) * S), o_ssum = take(8 * S), o_smax = take(4 * S);
     const size_t o_lso = take(4 * L1), o_gsubs = take(4 * G), o_gtick = take(4 * G);
     const size_t total = o + 8;
@@ -813,12 +817,56 @@ int awp_adt_step16(awp_plan *plan, const float *weights, uint8_t *packed,
 }
 
 namespace {
+// Arguments of the final reduction + rule for the batch whose partials are in `set`.
+adt::FinalRuleArgs final_rule_args(const awp_plan *plan, int set) {
+    const size_t n_partials = (size_t)plan->n_tiles * adt::kWavesPerBlock;
+    adt::FinalRuleArgs r;
+    r.partial_sumsq = plan->partial_sumsq + (size_t)set * n_partials;
+    r.partial_absmax = plan->partial_absmax + (size_t)set * n_partials;
+    r.subs = plan->subs;
+    r.layer_sub_off = plan->layer_sub_off;
+    r.group_subs = plan->group_subs;
+    r.group_ticket = plan->group_ticket;
+    r.sub_sumsq = plan->sub_sumsq;
+    r.sub_absmax = plan->sub_absmax;
+    r.stats = plan->stats;
+    r.group_off = plan->group_off;
+    r.n_subs = plan->n_subs;
+    r.l2_prev = plan->l2_prev;
+    r.bits = plan->bits;
+    r.counter = plan->counter;
+    r.rbytes = plan->rbytes;
+    r.changed = plan->changed;
+    // with tiles the fused kernel's first wavefront has set steps_done for the
+    // batch already and left the previous value in rule_seen[set]
+    r.seen = plan->n_tiles > 0 ? plan->rule_seen + set : plan->steps_done;
+    r.T = plan->T;
+    r.interval = plan->interval;
+    r.n_bits = plan->n_bits;
+    return r;
+}
+
+// Launches the final reduction + rule of a batch that has been waiting for it.
+int flush_pending(awp_plan *plan, hipStream_t hs) {
+    if (!plan->pending) return ADT_OK;
+    if (stream_is_capturing(hs))
+        return fail(ADT_EINVAL,
+                    "the last batch's statistics are still to be reduced: call awp_plan_read or "
+                    "awp_plan_get_state before capturing on this plan's stream");
+    hipError_t e = adt::launch_final_rule(final_rule_args(plan, plan->pending_set), hs);
+    if (e != hipSuccess) return fail_hip(e, "final + rule launch");
+    plan->pending = false;
+    return ADT_OK;
+}
+
 int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t packed_capacity,
               void *weights_out, int out_format, adt_stream_t stream) {
     if (!plan) return fail(ADT_EINVAL, "plan is null");
     hipStream_t hs = (hipStream_t)stream;
-    plan->last_stream = hs;
-    if (plan->n_layers == 0) return ADT_OK;
+    if (plan->n_layers == 0) {
+        plan->last_stream = hs;
+        return ADT_OK;
+    }
     if (plan->n > 0) {
         if (!weights || !packed) return fail(ADT_EINVAL, "null device pointer");
         const bool out16 = out_format == adt::kOutBf16 || out_format == adt::kOutFp16;
@@ -832,6 +880,42 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
     if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
     if (dev != plan->device) return fail(ADT_EINVAL, "plan belongs to another device");
 
+    const double out_bytes = out_format == adt::kOutFp32 ? 4.0 : out_format < 0 ? 0.0 : 2.0;
+    const LaunchShape shape =
+        shape_of(adt::kKernelFused,
+                 adt::fused_shape(plan->bytes_per_weight_hint + out_bytes, (int)out_bytes));
+
+    // Can a byte count move in this batch?  Only if the batch takes a group's
+    // interval counter to INTERVAL (Algorithm 1).  The status word says how large
+    // the largest counter was when some earlier batch began; that batch's
+    // predecessor may not have been reduced by then, and every batch issued since
+    // adds at most one.  If even that bound stays below INTERVAL - 1, nothing can
+    // move: the redo pass has nothing to do and this batch's final reduction and
+    // rule need not run before the next batch starts.  A stale or never-updated
+    // word only makes the bound larger.  Under graph capture the choice would be
+    // frozen into the graph and replays are not counted here: a plan that has
+    // been captured takes the in-order path from then on.
+    bool quiet = false;
+    if (plan->host_status && !plan->captured) {
+        if (stream_is_capturing(hs)) {
+            plan->captured = true;
+        } else {
+            const unsigned long long word = __atomic_load_n(plan->host_status, __ATOMIC_RELAXED);
+            const uint32_t begun = (uint32_t)(word >> 32), top = (uint32_t)word;
+            const uint32_t reduced = begun > 0u ? begun - 1u : 0u;
+            const uint64_t bound = (uint64_t)top + (uint32_t)(plan->issued - reduced);
+            quiet = bound + 1 < (uint64_t)plan->interval;
+        }
+    }
+    const bool carry = quiet && shape.waves == 1;    // one-wave blocks can carry sub-blocks
+    if (!carry) {
+        const int rc = flush_pending(plan, hs);      // in order from here on
+        if (rc) return rc;
+    }
+    plan->last_stream = hs;
+
+    const int set = plan->cur_set;
+    const size_t n_partials = (size_t)plan->n_tiles * adt::kWavesPerBlock;
     adt::FusedArgs a;
     a.weights = (const uint32_t *)weights;
     a.packed = packed;
@@ -840,11 +924,11 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
     a.pack_off = plan->pack_off;
     a.tile_off = plan->tile_off;
     a.rbytes = plan->rbytes;
-    a.partial_sumsq = plan->partial_sumsq;
-    a.partial_absmax = plan->partial_absmax;
+    a.partial_sumsq = plan->partial_sumsq + (size_t)set * n_partials;
+    a.partial_absmax = plan->partial_absmax + (size_t)set * n_partials;
     a.changed = plan->changed;
     a.steps_done = plan->steps_done;
-    a.rule_seen = plan->rule_seen;
+    a.rule_seen = plan->rule_seen + set;
     a.batch_count = plan->batch_count;
     a.counter = plan->counter;
     a.n_status_groups = plan->host_status ? plan->n_groups : 0;
@@ -852,65 +936,30 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
     a.stream_cache_limit = g_fused_cache_limit.load();
     a.n_layers = plan->n_layers;
     a.n_tiles = plan->n_tiles;
+    a.n_pending_subs = 0;
+    a.pending = final_rule_args(plan, plan->pending_set);
+    if (carry && plan->pending) a.n_pending_subs = (uint32_t)plan->n_subs;
 
     if (plan->n_tiles > 0) {
-        const double out_bytes = out_format == adt::kOutFp32 ? 4.0 : out_format < 0 ? 0.0 : 2.0;
-        const LaunchShape shape =
-            shape_of(adt::kKernelFused,
-                     adt::fused_shape(plan->bytes_per_weight_hint + out_bytes, (int)out_bytes));
         e = adt::launch_fused(a, out_format, shape.waves, shape.extra_lds, hs);
         if (e != hipSuccess) return fail_hip(e, "fused launch");
     }
-    adt::FinalRuleArgs r;
-    r.partial_sumsq = plan->partial_sumsq;
-    r.partial_absmax = plan->partial_absmax;
-    r.subs = plan->subs;
-    r.layer_sub_off = plan->layer_sub_off;
-    r.group_subs = plan->group_subs;
-    r.group_ticket = plan->group_ticket;
-    r.sub_sumsq = plan->sub_sumsq;
-    r.sub_absmax = plan->sub_absmax;
-    r.stats = plan->stats;
-    r.group_off = plan->group_off;
-    r.n_subs = plan->n_subs;
-    for (size_t i = 0; i < plan->host_subs.size(); ++i) r.inl_subs[i] = plan->host_subs[i];
-    r.l2_prev = plan->l2_prev;
-    r.bits = plan->bits;
-    r.counter = plan->counter;
-    r.rbytes = plan->rbytes;
-    r.changed = plan->changed;
-    // with tiles the fused kernel's first thread has set steps_done for this batch
-    // already and left the previous value in rule_seen
-    r.steps_done = plan->n_tiles > 0 ? plan->rule_seen : plan->steps_done;
-    r.T = plan->T;
-    r.interval = plan->interval;
-    r.n_bits = plan->n_bits;
+    ++plan->steps;
+    ++plan->issued;
+    plan->cur_set = set ^ 1;
+    if (carry) {
+        // this batch's reduction rides with the next batch (or is launched by
+        // whoever needs the state first)
+        plan->pending = true;
+        plan->pending_set = set;
+        return ADT_OK;
+    }
+    plan->pending = false;
     if (plan->n_subs > 0) {
-        e = adt::launch_final_rule(r, hs);
+        e = adt::launch_final_rule(final_rule_args(plan, set), hs);
         if (e != hipSuccess) return fail_hip(e, "final + rule launch");
     }
-    ++plan->steps;
-    // The redo pass has something to do only in a batch that takes a group's
-    // counter to INTERVAL.  The status word says how large the largest counter
-    // was after some earlier batch; every batch issued since adds at most one.
-    // If even that bound stays below INTERVAL - 1 before this batch, no byte
-    // count can move and the launch is left out.  A stale or never-updated word
-    // only makes the bound larger.  Under graph capture the decision would be
-    // frozen into the graph and replays are not counted here: always launch.
-    bool redo = true;
-    if (plan->host_status && !plan->captured) {
-        if (stream_is_capturing(hs)) {
-            plan->captured = true;
-        } else {
-            const unsigned long long word =
-                __atomic_load_n(plan->host_status, __ATOMIC_RELAXED);
-            const uint32_t begun = (uint32_t)(word >> 32), top = (uint32_t)word;
-            const uint64_t bound = (uint64_t)top + (uint32_t)(plan->issued - begun);
-            redo = bound + 1 >= (uint64_t)plan->interval;
-        }
-    }
-    ++plan->issued;
-    if (redo) {
+    if (!quiet) {
         e = adt::launch_redo(a, out_format, plan->pack_off, plan->packed_size, plan->steps_done, hs);
         if (e != hipSuccess) return fail_hip(e, "redo launch");
     }
@@ -918,10 +967,17 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
 }
 }  // namespace
 
+int awp_plan_flush(awp_plan *plan) {
+    if (!plan) return fail(ADT_EINVAL, "plan is null");
+    return flush_pending(plan, plan->last_stream);
+}
+
 int awp_plan_read(awp_plan *plan, double *stats, int32_t *bits, int32_t *counter,
                   uint8_t *bytes, int64_t *packed_size) {
     if (!plan) return fail(ADT_EINVAL, "plan is null");
     hipStream_t hs = plan->last_stream;
+    const int rc = flush_pending(plan, hs);
+    if (rc) return rc;
     const size_t L = (size_t)plan->n_layers;
     hipError_t e = hipSuccess;
     auto get = [&](void *dst, const void *src, size_t bytes_) {
@@ -945,6 +1001,8 @@ int awp_plan_get_state(awp_plan *plan, int32_t *bits, int32_t *counter, double *
                        int32_t *batches_seen) {
     if (!plan) return fail(ADT_EINVAL, "plan is null");
     hipStream_t hs = plan->last_stream;
+    const int rc = flush_pending(plan, hs);
+    if (rc) return rc;
     const size_t G = (size_t)plan->n_groups;
     hipError_t e = hipSuccess;
     auto get = [&](void *dst, const void *src, size_t n) {
@@ -979,6 +1037,8 @@ int awp_plan_set_state(awp_plan *plan, const int32_t *bits, const int32_t *count
     }
     pack_off[L] = p;
     const int32_t seen = batches_seen != 0;
+    const int rc = flush_pending(plan, plan->last_stream);    // its results are replaced below
+    if (rc) return rc;
     hipError_t e = hipStreamSynchronize(plan->last_stream);   // earlier steps still read the tables
     auto put = [&](void *dst, const void *src, size_t n) {
         if (n && e == hipSuccess) e = hipMemcpy(dst, src, n, hipMemcpyHostToDevice);

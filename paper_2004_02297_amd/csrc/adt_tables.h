@@ -191,6 +191,40 @@ struct AblationArgs {
     uint8_t rbytes[kInlineLayers];
 };
 
+// Final reduction of the statistics + Algorithm 1.  The partials of a layer
+// are cut into chunks of kFinalChunk; one wavefront ("sub-block") reduces one
+// chunk.  Every layer has at least one sub-block (an empty layer: an empty
+// chunk) and every group at least one (a group without layers: one that reduces
+// nothing), so that each group's rule runs.
+constexpr uint32_t kFinalChunk = 256;       // four partials per lane
+struct FinalSub {           // work of one sub-block
+    int32_t group;
+    int32_t layer;          // -1: the group has no layer
+    uint32_t begin, end;    // partials [begin, end) of that layer
+};
+struct FinalRuleArgs {
+    const double *partial_sumsq;    // the partials of the batch to reduce
+    const uint32_t *partial_absmax;
+    const FinalSub *subs;           // one per sub-block
+    const uint32_t *layer_sub_off;  // n_layers + 1: sub-blocks of layer l are [off[l], off[l+1])
+    const int32_t *group_subs;      // per group: number of its sub-blocks
+    int32_t *group_ticket;          // per group: sub-blocks finished in this pass (0 between passes)
+    double *sub_sumsq;              // one per sub-block
+    uint32_t *sub_absmax;
+    double *stats;              // n_layers x 3
+    const int32_t *group_off;   // n_groups + 1 layer indices
+    int n_subs;
+    double *l2_prev;            // per group
+    int32_t *bits;              // per group
+    int32_t *counter;           // per group
+    uint8_t *rbytes;            // per layer
+    int32_t *changed;
+    const int32_t *seen;        // 0 for the first batch: that batch only records norms
+    double T;
+    int interval;
+    int n_bits;
+};
+
 // Device-resident tables of a plan (see awp_fused.hip): everything is a
 // device pointer; tile_off counts block tiles of kBlockTile weights.
 struct FusedArgs {
@@ -201,56 +235,24 @@ struct FusedArgs {
     const int64_t *pack_off;
     const uint32_t *tile_off;
     const uint8_t *rbytes;
-    double *partial_sumsq;      // one per wave tile: 4 * n_tiles entries
+    double *partial_sumsq;      // one per wave tile: 4 * n_tiles entries (this batch's set)
     uint32_t *partial_absmax;
     int32_t *changed;           // cleared by the fused kernel, raised by the rule, read by redo
-    // Bookkeeping of a batch, done by the fused kernel's first thread before
+    // Bookkeeping of a batch, done by the fused kernel's first wavefront before
     // anything of the batch is reduced (see begin_batch in awp_fused.hip):
     int32_t *steps_done;        // non-zero once a batch has been processed
-    int32_t *rule_seen;         // steps_done as it was before this batch: what the rule reads
+    int32_t *rule_seen;         // steps_done as it was before this batch: what this batch's rule reads
     uint32_t *batch_count;      // batches begun since the plan was created or its state set
-    const int32_t *counter;     // per group: interval counters as the previous batch left them
+    const int32_t *counter;     // per group: interval counters (the previous batches' rule wrote them)
     int n_status_groups;        // number of groups if the status word is kept, else 0
     unsigned long long *host_status;   // pinned host word (batches << 32 | largest counter); may be null
     int64_t stream_cache_limit;   // streams larger than this are written nontemporal
     int n_layers;
     uint32_t n_tiles;
-};
-
-// Final reduction of the statistics + Algorithm 1.  The partials of a layer
-// are cut into chunks of kFinalChunk; one block ("sub-block") reduces one chunk.
-// Every layer has at least one sub-block (an empty layer: an empty chunk) and
-// every group at least one (a group without layers: one that reduces nothing),
-// so that each group's rule runs.
-constexpr uint32_t kFinalChunk = 8192;
-struct FinalSub {           // work of one sub-block
-    int32_t group;
-    int32_t layer;          // -1: the group has no layer
-    uint32_t begin, end;    // partials [begin, end) of that layer
-};
-constexpr int kFinalInlineSubs = 96;   // up to this many sub-blocks ride in the kernel arguments
-struct FinalRuleArgs {
-    const double *partial_sumsq;
-    const uint32_t *partial_absmax;
-    const FinalSub *subs;           // one per block of the launch (used beyond kFinalInlineSubs)
-    const uint32_t *layer_sub_off;  // n_layers + 1: sub-blocks of layer l are [off[l], off[l+1])
-    const int32_t *group_subs;      // per group: number of its sub-blocks
-    int32_t *group_ticket;          // per group: sub-blocks finished in this launch (0 between launches)
-    double *sub_sumsq;              // one per sub-block
-    uint32_t *sub_absmax;
-    double *stats;              // n_layers x 3
-    const int32_t *group_off;   // n_groups + 1 layer indices
-    int n_subs;                 // blocks of the launch
-    double *l2_prev;            // per group
-    int32_t *bits;              // per group
-    int32_t *counter;           // per group
-    uint8_t *rbytes;            // per layer
-    int32_t *changed;
-    const int32_t *steps_done;  // 0 before the first batch: that batch only records norms
-    double T;
-    int interval;
-    int n_bits;
-    FinalSub inl_subs[kFinalInlineSubs];
+    // The previous batch's final reduction and rule, carried along by the first
+    // n_pending_subs one-wave blocks of this launch (0: nothing is carried).
+    uint32_t n_pending_subs;
+    FinalRuleArgs pending;
 };
 
 // Redo pass: layers whose stream-offset table fits the kernel's LDS, and its grid.

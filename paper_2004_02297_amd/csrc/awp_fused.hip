@@ -125,6 +125,102 @@ __device__ __forceinline__ void fused_block_wave_tile(const FusedArgs &a, const 
     }
 }
 
+// Statistics of every layer, then Algorithm 1 for every group: the work of one
+// sub-block, done by one wavefront.  Phase 1: the wavefront reduces its chunk of
+// one layer's partials (fixed order) to a sub-partial.  Phase 2: the wavefront
+// that finishes last among the sub-blocks of a group (a ticket counter per
+// group; release / acquire fences around it, the one place in the library where
+// a block reads what another block of the same launch wrote) adds up each of the
+// group's layers from its sub-partials, again in an order fixed by the indices
+// alone, writes the statistics and runs the rule for the group.  Which
+// wavefront happens to be last has no influence on any result, and neither has
+// the launch the sub-blocks ride in (a kernel of their own, or the head of the
+// next batch's fused kernel).  All 64 lanes must be active.
+__device__ __forceinline__ void final_rule_wave(const FinalRuleArgs &a, uint32_t sub, int lane) {
+    const uint32_t *sub_words = (const uint32_t *)a.subs + 4 * (size_t)sub;   // a FinalSub
+    const int g = (int)table_load(sub_words, 0);
+    const int my_layer = (int)table_load(sub_words, 1);
+    const uint32_t begin = table_load(sub_words, 2), end = table_load(sub_words, 3);
+    const int n_subs = table_load(a.group_subs, g);
+    const int l0 = table_load(a.group_off, g), l1 = table_load(a.group_off, g + 1);
+    // what the rule will need, requested early so that it arrives behind the partials
+    int bits = 0, counter = 0, seen = 0;
+    double prev = 0.0;
+    if (lane == 0) {
+        bits = a.bits[g];
+        counter = a.counter[g];
+        prev = a.l2_prev[g];
+        seen = *a.seen;
+    }
+    double tot;
+    uint32_t tm;
+    wave_reduce_partials(a.partial_sumsq, a.partial_absmax, begin, end, lane, tot, tm);
+    double group_sumsq = 0.0;
+    if (n_subs == 1) {
+        // one sub-block, hence at most one layer: no exchange with other blocks
+        if (lane == 0 && my_layer >= 0) {
+            double *o = a.stats + (int64_t)my_layer * 3;
+            o[0] = tot;
+            o[1] = sqrt(tot);
+            o[2] = (double)__uint_as_float(tm);   // NaN bits stay NaN
+            group_sumsq = tot;
+        }
+    } else {
+        int is_last = 0;
+        if (lane == 0) {
+            a.sub_sumsq[sub] = tot;
+            a.sub_absmax[sub] = tm;
+            __threadfence();                                    // publish the sub-partial
+            const int ticket = atomicAdd(&a.group_ticket[g], 1);
+            is_last = ticket == n_subs - 1;
+        }
+        if (__builtin_amdgcn_readfirstlane(is_last) == 0) return;   // lane 0's verdict
+        __threadfence();                                        // see the other sub-partials
+        // The group's norm is the l2-norm over all weights of its layers: the
+        // layers' sums of squares added in index order.
+        for (int l = l0; l < l1; ++l) {
+            wave_reduce_partials(a.sub_sumsq, a.sub_absmax, table_load(a.layer_sub_off, l),
+                                 table_load(a.layer_sub_off, l + 1), lane, tot, tm);
+            if (lane == 0) {
+                double *o = a.stats + (int64_t)l * 3;
+                o[0] = tot;
+                o[1] = sqrt(tot);
+                o[2] = (double)__uint_as_float(tm);
+                group_sumsq += tot;
+            }
+        }
+        if (lane == 0) a.group_ticket[g] = 0;                   // ready for the next pass
+    }
+    if (lane != 0) return;
+    const double now = sqrt(group_sumsq);
+    if (seen != 0) {                        // the first batch only records its norm
+        const double delta =
+            prev == 0.0 ? (now == 0.0 ? 0.0 : __builtin_huge_val()) : (now - prev) / prev;
+        if (delta < a.T) ++counter;
+        if (counter == a.interval) {
+            bits += a.n_bits;
+            if (bits > 32) bits = 32;
+            counter = 0;
+        }
+        a.counter[g] = counter;
+        a.bits[g] = bits;
+    }
+    a.l2_prev[g] = now;
+    const int r = (bits + 7) >> 3;
+    bool moved = false;
+    for (int l = l0; l < l1; ++l) {
+        if (r != (int)a.rbytes[l]) {
+            a.rbytes[l] = (uint8_t)r;
+            moved = true;
+        }
+    }
+    if (moved) *a.changed = 1;              // benign race: every writer stores 1
+}
+
+__global__ __launch_bounds__(kWave) void final_rule_kernel(const FinalRuleArgs a) {
+    final_rule_wave(a, blockIdx.x, (int)threadIdx.x);
+}
+
 // The first wavefront, before anything of the batch is reduced: clears
 // `changed`, hands the rule the "has a batch been seen" flag as it was before
 // this batch, and publishes to the host how far the interval counters had got
@@ -163,7 +259,16 @@ __global__ __launch_bounds__(WAVES * kWave) void fused_kernel(const FusedArgs a)
     __shared__ __attribute__((aligned(16))) uint32_t smem[WAVES][kWaveLdsDw];
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
-    const uint32_t wt = WAVES == 1 ? blockIdx.x : blockIdx.x * (uint32_t)kWavesPerBlock + (uint32_t)wave;
+    uint32_t block = blockIdx.x;
+    if (WAVES == 1 && a.n_pending_subs != 0u) {
+        // the head of the grid carries the previous batch's final reduction and rule
+        if (block < a.n_pending_subs) {
+            final_rule_wave(a.pending, block, lane);
+            return;
+        }
+        block -= a.n_pending_subs;
+    }
+    const uint32_t wt = WAVES == 1 ? block : block * (uint32_t)kWavesPerBlock + (uint32_t)wave;
     if (wt == 0) begin_batch(a, lane);        // wave uniform
     const BlockTileRef t = find_block_tile(a, wt / kWavesPerBlock);
     const bool nt = table_load(a.pack_off, a.n_layers) > a.stream_cache_limit;   // whole stream
@@ -177,99 +282,6 @@ __global__ __launch_bounds__(WAVES * kWave) void fused_kernel(const FusedArgs a)
         a.partial_sumsq[wt] = sum;
         a.partial_absmax[wt] = mag;
     }
-}
-
-// Statistics of every layer, then Algorithm 1 for every group, in one launch.
-// Phase 1: each block reduces one chunk of one layer's partials (fixed order)
-// to a sub-partial.  Phase 2: the block that finishes last among the blocks of
-// a group (a ticket counter per group; release / acquire fences around it, the
-// one place in the library where a block reads what another block of the same
-// launch wrote) adds up each of the group's layers from its sub-partials, again
-// in an order fixed by the indices alone, writes the statistics and runs the
-// rule for the group.  Which block happens to be last has no influence on any
-// result.
-template <bool INLINE>
-__global__ __launch_bounds__(kFinalBlock) void final_rule_kernel(const FinalRuleArgs a) {
-    __shared__ int is_last;
-    const FinalSub me = INLINE ? a.inl_subs[blockIdx.x] : a.subs[blockIdx.x];
-    const int g = me.group;
-    // what the rule will need, requested early so that it arrives behind the partials
-    int bits = 0, counter = 0, n_subs = 0, seen = 0;
-    double prev = 0.0;
-    if (threadIdx.x == 0) {
-        n_subs = a.group_subs[g];
-        bits = a.bits[g];
-        counter = a.counter[g];
-        prev = a.l2_prev[g];
-        seen = *a.steps_done;
-    }
-    double tot;
-    uint32_t tm;
-    reduce_partials(a.partial_sumsq, a.partial_absmax, me.begin, me.end, tot, tm);
-    const int l0 = a.group_off[g], l1 = a.group_off[g + 1];
-    double group_sumsq = 0.0;
-    if (threadIdx.x == 0) is_last = n_subs;      // 1: this block is the group's only one
-    __syncthreads();
-    if (is_last == 1) {
-        // one sub-block, hence at most one layer: no exchange with other blocks
-        if (threadIdx.x == 0 && me.layer >= 0) {
-            double *o = a.stats + (int64_t)me.layer * 3;
-            o[0] = tot;
-            o[1] = sqrt(tot);
-            o[2] = (double)__uint_as_float(tm);   // NaN bits stay NaN
-            group_sumsq = tot;
-        }
-    } else {
-        __syncthreads();                                        // everyone has read is_last
-        if (threadIdx.x == 0) {
-            a.sub_sumsq[blockIdx.x] = tot;
-            a.sub_absmax[blockIdx.x] = tm;
-            __threadfence();                                    // publish the sub-partial
-            const int ticket = atomicAdd(&a.group_ticket[g], 1);
-            is_last = ticket == n_subs - 1;
-        }
-        __syncthreads();
-        if (!is_last) return;
-        __threadfence();                                        // see the other blocks' sub-partials
-        // The group's norm is the l2-norm over all weights of its layers: the
-        // layers' sums of squares added in index order.
-        for (int l = l0; l < l1; ++l) {
-            reduce_partials(a.sub_sumsq, a.sub_absmax, a.layer_sub_off[l], a.layer_sub_off[l + 1], tot,
-                            tm);
-            if (threadIdx.x == 0) {
-                double *o = a.stats + (int64_t)l * 3;
-                o[0] = tot;
-                o[1] = sqrt(tot);
-                o[2] = (double)__uint_as_float(tm);
-                group_sumsq += tot;
-            }
-        }
-        if (threadIdx.x == 0) a.group_ticket[g] = 0;            // ready for the next launch
-    }
-    if (threadIdx.x != 0) return;
-    const double now = sqrt(group_sumsq);
-    if (seen != 0) {                        // the first batch only records its norm
-        const double delta =
-            prev == 0.0 ? (now == 0.0 ? 0.0 : __builtin_huge_val()) : (now - prev) / prev;
-        if (delta < a.T) ++counter;
-        if (counter == a.interval) {
-            bits += a.n_bits;
-            if (bits > 32) bits = 32;
-            counter = 0;
-        }
-        a.counter[g] = counter;
-        a.bits[g] = bits;
-    }
-    a.l2_prev[g] = now;
-    const int r = (bits + 7) >> 3;
-    bool moved = false;
-    for (int l = l0; l < l1; ++l) {
-        if (r != (int)a.rbytes[l]) {
-            a.rbytes[l] = (uint8_t)r;
-            moved = true;
-        }
-    }
-    if (moved) *a.changed = 1;              // benign race: every writer stores 1
 }
 
 // Stream offsets of the current byte counts: exclusive prefix sum of n_l * r_l
@@ -381,8 +393,9 @@ static hipError_t launch_fused_w(const FusedArgs &a, int out_format, uint32_t ex
                            : out_format == kOutFp32 ? fused_kernel<kOutFp32, WAVES>
                            : out_format == kOutBf16 ? fused_kernel<kOutBf16, WAVES>
                                                     : fused_kernel<kOutFp16, WAVES>;
-    return launch(k, kKernelFused, a.n_tiles * (uint32_t)(kWavesPerBlock / WAVES), WAVES * kWave,
-                  stream, a, extra_lds);
+    const uint32_t carried = WAVES == 1 ? a.n_pending_subs : 0u;
+    return launch(k, kKernelFused, a.n_tiles * (uint32_t)(kWavesPerBlock / WAVES) + carried,
+                  WAVES * kWave, stream, a, extra_lds);
 }
 
 // out_format: kOutNone, kOutFp32, kOutBf16 or kOutFp16; waves: 1 or 4
@@ -393,11 +406,7 @@ hipError_t launch_fused(const FusedArgs &a, int out_format, int waves, uint32_t 
 }
 
 hipError_t launch_final_rule(const FinalRuleArgs &a, hipStream_t stream) {
-    return a.n_subs <= kFinalInlineSubs
-               ? launch(final_rule_kernel<true>, kKernelFinalRule, (uint32_t)a.n_subs, kFinalBlock,
-                        stream, a)
-               : launch(final_rule_kernel<false>, kKernelFinalRule, (uint32_t)a.n_subs, kFinalBlock,
-                        stream, a);
+    return launch(final_rule_kernel, kKernelFinalRule, (uint32_t)a.n_subs, kWave, stream, a);
 }
 
 template <typename... A>

@@ -74,6 +74,38 @@ __device__ __forceinline__ void square_add(uint32_t bits, double &acc, uint32_t 
     mag = m > mag ? m : mag;
 }
 
+// One wavefront adds partials [begin, end) in an order fixed by the indices
+// alone: lane t takes begin+t, begin+t+64, ... (eight loads in flight per
+// round), then the lanes are combined by wave_sum / wave_max.  Every lane
+// returns the result.  All 64 lanes must be active.  The partials may have been
+// written by other blocks of the same launch (after a fence): ordinary loads.
+__device__ __forceinline__ void wave_reduce_partials(const double *partial_sumsq,
+                                                     const uint32_t *partial_absmax,
+                                                     uint32_t begin, uint32_t end, int lane,
+                                                     double &sumsq, uint32_t &magnitude) {
+    constexpr int kInFlight = 8;
+    double acc = 0.0;
+    uint32_t mag = 0u;
+    for (uint32_t base = begin; base < end; base += kInFlight * kWave) {   // wave uniform
+        double v[kInFlight];
+        uint32_t m[kInFlight];
+#pragma unroll
+        for (int j = 0; j < kInFlight; ++j) {
+            const uint32_t k = base + (uint32_t)(j * kWave + lane);
+            const bool ok = k < end;
+            v[j] = ok ? partial_sumsq[k] : 0.0;
+            m[j] = ok ? partial_absmax[k] : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < kInFlight; ++j) {
+            acc += v[j];
+            mag = m[j] > mag ? m[j] : mag;
+        }
+    }
+    sumsq = wave_sum(acc);
+    magnitude = wave_max(mag);
+}
+
 // One block of kFinalBlock threads adds partials [begin, end) in an order fixed
 // by the indices alone: thread t takes begin+t, begin+t+1024, ... (sixteen loads
 // in flight per round), a wave combines its lanes with xor-shuffles, thread 0
