@@ -192,11 +192,18 @@ struct AblationArgs {
 };
 
 // Final reduction of the statistics + Algorithm 1.  The partials of a layer
-// are cut into chunks of kFinalChunk; one wavefront ("sub-block") reduces one
-// chunk.  Every layer has at least one sub-block (an empty layer: an empty
-// chunk) and every group at least one (a group without layers: one that reduces
-// nothing), so that each group's rule runs.
-constexpr uint32_t kFinalChunk = 256;       // four partials per lane
+// are cut into chunks of kFinalChunk, the work of one "sub-block"; a chunk is
+// kFinalSlices slices of kFinalSlice partials.  A slice is summed by one
+// wavefront (eight partials per lane, then across the lanes), the slices of a
+// chunk are added in index order.  That order does not depend on who does the
+// work: the sixteen wavefronts of a block, one slice each (the kernel of its
+// own), or one wavefront walking the slices (a sub-block carried at the head of
+// the next batch's fused kernel).  Every layer has at least one sub-block (an
+// empty layer: an empty chunk) and every group at least one (a group without
+// layers: one that reduces nothing), so that each group's rule runs.
+constexpr uint32_t kFinalSlice = 512;
+constexpr int kFinalSlices = 16;
+constexpr uint32_t kFinalChunk = kFinalSlice * kFinalSlices;
 struct FinalSub {           // work of one sub-block
     int32_t group;
     int32_t layer;          // -1: the group has no layer

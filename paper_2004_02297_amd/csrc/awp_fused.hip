@@ -11,17 +11,22 @@
 //                          of its own, its top r bytes go to the packed stream
 //                          and the truncated words (what Bitunpack would
 //                          return) go to the output weights.
-//   2. final+rule kernel : the partials of every layer are reduced in a fixed
-//                          order (big layers by several blocks), then Algorithm
-//                          1 runs per layer group: new bit count, interval
-//                          counter, byte counts of the group's layers, and the
-//                          flag `changed` if a byte count moved.
+//   2. final + rule      : the partials of every layer are reduced in a fixed
+//                          order (big layers by several sub-blocks), then
+//                          Algorithm 1 runs per layer group: new bit count,
+//                          interval counter, byte counts of the group's layers,
+//                          and the flag `changed` if a byte count moved.
 //   3. redo kernel       : a small grid that returns at once unless `changed`
 //                          is set; then every block rebuilds the stream offsets
 //                          (prefix sum of n_l * r_l) and the grid packs and
 //                          truncates again with the new byte counts.
 // The result is what statistics -> rule -> pack -> unpack would give in that
 // order, whether or not the speculation held.
+//
+// While the host can prove that no byte count can move in a batch (no interval
+// counter can reach INTERVAL: see begin_batch and plan_step), step 3 is not
+// launched and step 2 does not get a launch of its own: its sub-blocks ride at
+// the head of the NEXT batch's fused kernel, so that a batch is one launch.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -125,62 +130,95 @@ __device__ __forceinline__ void fused_block_wave_tile(const FusedArgs &a, const 
     }
 }
 
-// Statistics of every layer, then Algorithm 1 for every group: the work of one
-// sub-block, done by one wavefront.  Phase 1: the wavefront reduces its chunk of
-// one layer's partials (fixed order) to a sub-partial.  Phase 2: the wavefront
-// that finishes last among the sub-blocks of a group (a ticket counter per
-// group; release / acquire fences around it, the one place in the library where
-// a block reads what another block of the same launch wrote) adds up each of the
-// group's layers from its sub-partials, again in an order fixed by the indices
-// alone, writes the statistics and runs the rule for the group.  Which
-// wavefront happens to be last has no influence on any result, and neither has
-// the launch the sub-blocks ride in (a kernel of their own, or the head of the
-// next batch's fused kernel).  All 64 lanes must be active.
-__device__ __forceinline__ void final_rule_wave(const FinalRuleArgs &a, uint32_t sub, int lane) {
+// Statistics of every layer, then Algorithm 1 for every group.  Phase 1: a
+// sub-block reduces its chunk of one layer's partials (fixed order, see
+// kFinalChunk) to a sub-partial.  Phase 2: the sub-block that finishes last
+// among the sub-blocks of a group (a ticket counter per group, the one place in
+// the library where a block reads what another block of the same launch wrote)
+// adds up each of the group's layers
+// from its sub-partials, again in an order fixed by the indices alone, writes
+// the statistics and runs the rule for the group.  Which sub-block happens to be
+// last has no influence on any result, and neither has the launch the sub-blocks
+// ride in (a kernel of their own, or the head of the next batch's fused
+// kernel).
+struct FinalWork {          // what a sub-block's first wavefront knows before the reduction
+    int g, layer, n_subs, l0, l1;
+    uint32_t begin, end;
+    int bits, counter, seen;    // lane 0 only
+    double prev;                // lane 0 only
+};
+
+__device__ __forceinline__ FinalWork final_work(const FinalRuleArgs &a, uint32_t sub, int lane) {
     const uint32_t *sub_words = (const uint32_t *)a.subs + 4 * (size_t)sub;   // a FinalSub
-    const int g = (int)table_load(sub_words, 0);
-    const int my_layer = (int)table_load(sub_words, 1);
-    const uint32_t begin = table_load(sub_words, 2), end = table_load(sub_words, 3);
-    const int n_subs = table_load(a.group_subs, g);
-    const int l0 = table_load(a.group_off, g), l1 = table_load(a.group_off, g + 1);
+    FinalWork w;
+    w.g = (int)table_load(sub_words, 0);
+    w.layer = (int)table_load(sub_words, 1);
+    w.begin = table_load(sub_words, 2);
+    w.end = table_load(sub_words, 3);
+    w.n_subs = table_load(a.group_subs, w.g);
+    w.l0 = table_load(a.group_off, w.g);
+    w.l1 = table_load(a.group_off, w.g + 1);
     // what the rule will need, requested early so that it arrives behind the partials
-    int bits = 0, counter = 0, seen = 0;
-    double prev = 0.0;
+    w.bits = w.counter = w.seen = 0;
+    w.prev = 0.0;
     if (lane == 0) {
-        bits = a.bits[g];
-        counter = a.counter[g];
-        prev = a.l2_prev[g];
-        seen = *a.seen;
+        w.bits = a.bits[w.g];
+        w.counter = a.counter[w.g];
+        w.prev = a.l2_prev[w.g];
+        w.seen = *a.seen;
     }
-    double tot;
-    uint32_t tm;
-    wave_reduce_partials(a.partial_sumsq, a.partial_absmax, begin, end, lane, tot, tm);
+    return w;
+}
+
+// Slice i of a chunk [begin, end): one wavefront, every lane returns the result.
+__device__ __forceinline__ void reduce_slice(const FinalRuleArgs &a, const FinalWork &w, int i,
+                                             int lane, double &sumsq, uint32_t &magnitude) {
+    const uint32_t from = w.begin + (uint32_t)i * kFinalSlice;
+    const uint32_t to = w.end - from > kFinalSlice ? from + kFinalSlice : w.end;
+    sumsq = 0.0;
+    magnitude = 0u;
+    if (from < w.end)       // wave uniform
+        wave_reduce_partials(a.partial_sumsq, a.partial_absmax, from, to, lane, sumsq, magnitude);
+}
+
+// Everything after the chunk's total (tot, tm: the same in all 64 lanes of the
+// one wavefront that calls this).
+__device__ __forceinline__ void final_rule_tail(const FinalRuleArgs &a, const FinalWork &w,
+                                                uint32_t sub, int lane, double tot, uint32_t tm) {
+    const int g = w.g;
     double group_sumsq = 0.0;
-    if (n_subs == 1) {
+    if (w.n_subs == 1) {
         // one sub-block, hence at most one layer: no exchange with other blocks
-        if (lane == 0 && my_layer >= 0) {
-            double *o = a.stats + (int64_t)my_layer * 3;
+        if (lane == 0 && w.layer >= 0) {
+            double *o = a.stats + (int64_t)w.layer * 3;
             o[0] = tot;
             o[1] = sqrt(tot);
             o[2] = (double)__uint_as_float(tm);   // NaN bits stay NaN
             group_sumsq = tot;
         }
     } else {
+        // The sub-partial is handed over through device-scope atomics, which act
+        // where all XCDs see them: two exchanges, and only when both have returned
+        // (the empty asm statement consumes their results) the ticket is drawn.  The
+        // last sub-block reads the sub-partials with device-scope atomic loads.  No
+        // cache is written back or invalidated on the way; a release / acquire fence
+        // pair here stalls the whole memory system for some 80 ns, which the fused
+        // kernel that carries these sub-blocks would pay for.
         int is_last = 0;
         if (lane == 0) {
-            a.sub_sumsq[sub] = tot;
-            a.sub_absmax[sub] = tm;
-            __threadfence();                                    // publish the sub-partial
+            const unsigned long long was_s = atomicExch(
+                (unsigned long long *)(a.sub_sumsq + sub), (unsigned long long)__double_as_longlong(tot));
+            const uint32_t was_m = atomicExch(a.sub_absmax + sub, tm);
+            asm volatile("" ::"v"((uint32_t)was_s), "v"((uint32_t)(was_s >> 32)), "v"(was_m) : "memory");
             const int ticket = atomicAdd(&a.group_ticket[g], 1);
-            is_last = ticket == n_subs - 1;
+            is_last = ticket == w.n_subs - 1;
         }
         if (__builtin_amdgcn_readfirstlane(is_last) == 0) return;   // lane 0's verdict
-        __threadfence();                                        // see the other sub-partials
         // The group's norm is the l2-norm over all weights of its layers: the
         // layers' sums of squares added in index order.
-        for (int l = l0; l < l1; ++l) {
-            wave_reduce_partials(a.sub_sumsq, a.sub_absmax, table_load(a.layer_sub_off, l),
-                                 table_load(a.layer_sub_off, l + 1), lane, tot, tm);
+        for (int l = w.l0; l < w.l1; ++l) {
+            wave_reduce_partials<true>(a.sub_sumsq, a.sub_absmax, table_load(a.layer_sub_off, l),
+                                       table_load(a.layer_sub_off, l + 1), lane, tot, tm);
             if (lane == 0) {
                 double *o = a.stats + (int64_t)l * 3;
                 o[0] = tot;
@@ -192,10 +230,11 @@ __device__ __forceinline__ void final_rule_wave(const FinalRuleArgs &a, uint32_t
         if (lane == 0) a.group_ticket[g] = 0;                   // ready for the next pass
     }
     if (lane != 0) return;
+    int bits = w.bits, counter = w.counter;
     const double now = sqrt(group_sumsq);
-    if (seen != 0) {                        // the first batch only records its norm
+    if (w.seen != 0) {                      // the first batch only records its norm
         const double delta =
-            prev == 0.0 ? (now == 0.0 ? 0.0 : __builtin_huge_val()) : (now - prev) / prev;
+            w.prev == 0.0 ? (now == 0.0 ? 0.0 : __builtin_huge_val()) : (now - w.prev) / w.prev;
         if (delta < a.T) ++counter;
         if (counter == a.interval) {
             bits += a.n_bits;
@@ -208,7 +247,7 @@ __device__ __forceinline__ void final_rule_wave(const FinalRuleArgs &a, uint32_t
     a.l2_prev[g] = now;
     const int r = (bits + 7) >> 3;
     bool moved = false;
-    for (int l = l0; l < l1; ++l) {
+    for (int l = w.l0; l < w.l1; ++l) {
         if (r != (int)a.rbytes[l]) {
             a.rbytes[l] = (uint8_t)r;
             moved = true;
@@ -217,8 +256,47 @@ __device__ __forceinline__ void final_rule_wave(const FinalRuleArgs &a, uint32_t
     if (moved) *a.changed = 1;              // benign race: every writer stores 1
 }
 
-__global__ __launch_bounds__(kWave) void final_rule_kernel(const FinalRuleArgs a) {
-    final_rule_wave(a, blockIdx.x, (int)threadIdx.x);
+// A sub-block done by one wavefront (all 64 lanes active): the slices one after
+// the other.
+__device__ __forceinline__ void final_rule_wave(const FinalRuleArgs &a, uint32_t sub, int lane) {
+    const FinalWork w = final_work(a, sub, lane);
+    double tot = 0.0;
+    uint32_t tm = 0u;
+    for (int i = 0; i < kFinalSlices; ++i) {
+        double s;
+        uint32_t m;
+        reduce_slice(a, w, i, lane, s, m);
+        tot += s;
+        tm = m > tm ? m : tm;
+    }
+    final_rule_tail(a, w, sub, lane, tot, tm);
+}
+
+// A sub-block done by a block of sixteen wavefronts: one slice each, then the
+// first wavefront adds the slice sums in index order and goes on alone.
+__global__ __launch_bounds__(kFinalBlock) void final_rule_kernel(const FinalRuleArgs a) {
+    static_assert(kFinalBlock == kFinalSlices * kWave, "one wavefront per slice");
+    __shared__ double slice_sum[kFinalSlices];
+    __shared__ uint32_t slice_mag[kFinalSlices];
+    const int lane = (int)(threadIdx.x & 63), wave = (int)(threadIdx.x >> 6);
+    const FinalWork w = final_work(a, blockIdx.x, wave == 0 ? lane : 1);   // state: first lane only
+    double s;
+    uint32_t m;
+    reduce_slice(a, w, wave, lane, s, m);
+    if (lane == 0) {
+        slice_sum[wave] = s;
+        slice_mag[wave] = m;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    double tot = 0.0;
+    uint32_t tm = 0u;
+#pragma unroll
+    for (int i = 0; i < kFinalSlices; ++i) {
+        tot += slice_sum[i];
+        tm = slice_mag[i] > tm ? slice_mag[i] : tm;
+    }
+    final_rule_tail(a, w, blockIdx.x, lane, tot, tm);
 }
 
 // The first wavefront, before anything of the batch is reduced: clears
@@ -406,7 +484,7 @@ hipError_t launch_fused(const FusedArgs &a, int out_format, int waves, uint32_t 
 }
 
 hipError_t launch_final_rule(const FinalRuleArgs &a, hipStream_t stream) {
-    return launch(final_rule_kernel, kKernelFinalRule, (uint32_t)a.n_subs, kWave, stream, a);
+    return launch(final_rule_kernel, kKernelFinalRule, (uint32_t)a.n_subs, kFinalBlock, stream, a);
 }
 
 template <typename... A>

@@ -77,8 +77,10 @@ __device__ __forceinline__ void square_add(uint32_t bits, double &acc, uint32_t 
 // One wavefront adds partials [begin, end) in an order fixed by the indices
 // alone: lane t takes begin+t, begin+t+64, ... (eight loads in flight per
 // round), then the lanes are combined by wave_sum / wave_max.  Every lane
-// returns the result.  All 64 lanes must be active.  The partials may have been
-// written by other blocks of the same launch (after a fence): ordinary loads.
+// returns the result.  All 64 lanes must be active.  COHERENT: the partials were
+// handed over by other blocks of the same launch through device-scope atomic
+// exchanges and are read with device-scope atomic loads (no cache in between).
+template <bool COHERENT = false>
 __device__ __forceinline__ void wave_reduce_partials(const double *partial_sumsq,
                                                      const uint32_t *partial_absmax,
                                                      uint32_t begin, uint32_t end, int lane,
@@ -93,8 +95,20 @@ __device__ __forceinline__ void wave_reduce_partials(const double *partial_sumsq
         for (int j = 0; j < kInFlight; ++j) {
             const uint32_t k = base + (uint32_t)(j * kWave + lane);
             const bool ok = k < end;
-            v[j] = ok ? partial_sumsq[k] : 0.0;
-            m[j] = ok ? partial_absmax[k] : 0u;
+            if (COHERENT) {
+                v[j] = 0.0;
+                m[j] = 0u;
+                if (ok) {
+                    v[j] = __longlong_as_double((long long)__hip_atomic_load(
+                        (const unsigned long long *)(partial_sumsq + k), __ATOMIC_RELAXED,
+                        __HIP_MEMORY_SCOPE_AGENT));
+                    m[j] = __hip_atomic_load(partial_absmax + k, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+                }
+            } else {
+                v[j] = ok ? partial_sumsq[k] : 0.0;
+                m[j] = ok ? partial_absmax[k] : 0u;
+            }
         }
 #pragma unroll
         for (int j = 0; j < kInFlight; ++j) {
