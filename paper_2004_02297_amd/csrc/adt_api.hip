@@ -74,8 +74,9 @@ struct awp_plan {
     int cur_set = 0, pending_set = 0;
     bool pending = false;
     double *l2_prev = nullptr, *stats = nullptr, *partial_sumsq = nullptr;
-    // final reduction + rule: its sub-blocks (see adt::FinalSub)
+    // final reduction + rule: its sub-blocks (see adt::FinalSub) and the slices per chunk
     int n_subs = 0;
+    int final_slices = 1;
     adt::FinalSub *subs = nullptr;
     uint32_t *layer_sub_off = nullptr, *sub_absmax = nullptr;
     int32_t *group_subs = nullptr, *group_ticket = nullptr;
@@ -695,6 +696,8 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
 
     // sub-blocks of the final + rule kernel: first every layer's chunks in layer
     // order, then one empty sub-block for every group that has no layer
+    pl->final_slices = adt::final_slices_for((uint64_t)pl->n_tiles * adt::kWavesPerBlock);
+    const uint32_t chunk = (uint32_t)pl->final_slices * adt::kFinalSlice;
     std::vector<adt::FinalSub> subs;
     std::vector<uint32_t> layer_sub_off(L1);
     std::vector<int32_t> group_subs(G, 0);
@@ -704,7 +707,7 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
             const uint32_t end = tile_off[(size_t)l + 1] * adt::kWavesPerBlock;
             uint32_t at = tile_off[(size_t)l] * adt::kWavesPerBlock;
             do {
-                const uint32_t stop = end - at > adt::kFinalChunk ? at + adt::kFinalChunk : end;
+                const uint32_t stop = end - at > chunk ? at + chunk : end;
                 subs.push_back(adt::FinalSub{(int32_t)g, l, at, stop});
                 ++group_subs[g];
                 at = stop;
@@ -832,6 +835,7 @@ adt::FinalRuleArgs final_rule_args(const awp_plan *plan, int set) {
     r.stats = plan->stats;
     r.group_off = plan->group_off;
     r.n_subs = plan->n_subs;
+    r.n_slices = plan->final_slices;
     r.l2_prev = plan->l2_prev;
     r.bits = plan->bits;
     r.counter = plan->counter;

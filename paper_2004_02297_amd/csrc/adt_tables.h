@@ -192,8 +192,8 @@ struct AblationArgs {
 };
 
 // Final reduction of the statistics + Algorithm 1.  The partials of a layer
-// are cut into chunks of kFinalChunk, the work of one "sub-block"; a chunk is
-// kFinalSlices slices of kFinalSlice partials.  A slice is summed by one
+// are cut into chunks, the work of one "sub-block"; a chunk is n_slices slices
+// of kFinalSlice partials.  A slice is summed by one
 // wavefront (eight partials per lane, then across the lanes), the slices of a
 // chunk are added in index order.  That order does not depend on who does the
 // work: the sixteen wavefronts of a block, one slice each (the kernel of its
@@ -201,9 +201,15 @@ struct AblationArgs {
 // the next batch's fused kernel).  Every layer has at least one sub-block (an
 // empty layer: an empty chunk) and every group at least one (a group without
 // layers: one that reduces nothing), so that each group's rule runs.
+// A plan picks the slices per chunk (1 .. kFinalMaxSlices) from its size, so
+// that a carried sub-block, whose one wavefront needs a memory round trip per
+// slice, stays short next to the fused kernel that carries it.
 constexpr uint32_t kFinalSlice = 512;
-constexpr int kFinalSlices = 16;
-constexpr uint32_t kFinalChunk = kFinalSlice * kFinalSlices;
+constexpr int kFinalMaxSlices = 16;
+inline int final_slices_for(uint64_t n_partials) {      // aims at about 32 sub-blocks of big layers
+    const uint64_t want = (n_partials + 32 * kFinalSlice - 1) / (32 * kFinalSlice);
+    return want < 1 ? 1 : want > (uint64_t)kFinalMaxSlices ? kFinalMaxSlices : (int)want;
+}
 struct FinalSub {           // work of one sub-block
     int32_t group;
     int32_t layer;          // -1: the group has no layer
@@ -221,6 +227,7 @@ struct FinalRuleArgs {
     double *stats;              // n_layers x 3
     const int32_t *group_off;   // n_groups + 1 layer indices
     int n_subs;
+    int n_slices;               // slices per chunk
     double *l2_prev;            // per group
     int32_t *bits;              // per group
     int32_t *counter;           // per group

@@ -132,7 +132,7 @@ __device__ __forceinline__ void fused_block_wave_tile(const FusedArgs &a, const 
 
 // Statistics of every layer, then Algorithm 1 for every group.  Phase 1: a
 // sub-block reduces its chunk of one layer's partials (fixed order, see
-// kFinalChunk) to a sub-partial.  Phase 2: the sub-block that finishes last
+// kFinalSlice) to a sub-partial.  Phase 2: the sub-block that finishes last
 // among the sub-blocks of a group (a ticket counter per group, the one place in
 // the library where a block reads what another block of the same launch wrote)
 // adds up each of the group's layers
@@ -262,7 +262,7 @@ __device__ __forceinline__ void final_rule_wave(const FinalRuleArgs &a, uint32_t
     const FinalWork w = final_work(a, sub, lane);
     double tot = 0.0;
     uint32_t tm = 0u;
-    for (int i = 0; i < kFinalSlices; ++i) {
+    for (int i = 0; i < a.n_slices; ++i) {
         double s;
         uint32_t m;
         reduce_slice(a, w, i, lane, s, m);
@@ -272,27 +272,28 @@ __device__ __forceinline__ void final_rule_wave(const FinalRuleArgs &a, uint32_t
     final_rule_tail(a, w, sub, lane, tot, tm);
 }
 
-// A sub-block done by a block of sixteen wavefronts: one slice each, then the
-// first wavefront adds the slice sums in index order and goes on alone.
+// A sub-block done by a block of up to sixteen wavefronts: one slice each, then
+// the first wavefront adds the slice sums in index order and goes on alone.
 __global__ __launch_bounds__(kFinalBlock) void final_rule_kernel(const FinalRuleArgs a) {
-    static_assert(kFinalBlock == kFinalSlices * kWave, "one wavefront per slice");
-    __shared__ double slice_sum[kFinalSlices];
-    __shared__ uint32_t slice_mag[kFinalSlices];
+    static_assert(kFinalBlock == kFinalMaxSlices * kWave, "one wavefront per slice");
+    __shared__ double slice_sum[kFinalMaxSlices];
+    __shared__ uint32_t slice_mag[kFinalMaxSlices];
     const int lane = (int)(threadIdx.x & 63), wave = (int)(threadIdx.x >> 6);
     const FinalWork w = final_work(a, blockIdx.x, wave == 0 ? lane : 1);   // state: first lane only
-    double s;
-    uint32_t m;
-    reduce_slice(a, w, wave, lane, s, m);
-    if (lane == 0) {
-        slice_sum[wave] = s;
-        slice_mag[wave] = m;
+    if (wave < a.n_slices) {
+        double s;
+        uint32_t m;
+        reduce_slice(a, w, wave, lane, s, m);
+        if (lane == 0) {
+            slice_sum[wave] = s;
+            slice_mag[wave] = m;
+        }
     }
     __syncthreads();
     if (wave != 0) return;
     double tot = 0.0;
     uint32_t tm = 0u;
-#pragma unroll
-    for (int i = 0; i < kFinalSlices; ++i) {
+    for (int i = 0; i < a.n_slices; ++i) {
         tot += slice_sum[i];
         tm = slice_mag[i] > tm ? slice_mag[i] : tm;
     }

@@ -560,6 +560,41 @@ def test_plan_state_does_not_depend_on_where_the_final_reduction_ran(adt):
     b.close()
 
 
+@pytest.mark.parametrize("big", [8_400_000, 40_000_000])
+def test_carried_reduction_of_one_big_layer(adt, big):
+    """A layer of many sub-blocks in a small plan (one slice per chunk) and in a
+    medium one (three slices per chunk): every batch's reduction is carried by the
+    next batch's kernel; state and statistics of the last batch against the oracle."""
+    sizes = [5000, big, 70000]
+    off = workloads.offsets_from_sizes(sizes)
+    N = int(off[-1])
+    rng = np.random.default_rng(73)
+    hw = rng.standard_normal(N).astype(np.float32) * np.float32(0.05)
+    w = torch.from_numpy(hw).cuda()
+    packed = torch.zeros(4 * N, dtype=torch.uint8, device="cuda")
+    out = torch.zeros(N, dtype=torch.float32, device="cuda")
+    plan = adt.AwpPlan(off, 0.0, 300, 8)
+    ost = oracle.AwpState(3, 8)
+    steps = 5
+    for i in range(steps):
+        if i:
+            w.mul_(0.98)
+        plan.step(w, packed, out)
+    for i in range(steps):                       # the oracle follows the same weights
+        hwi = (torch.from_numpy(hw) * 1.0)
+        for _ in range(i):
+            hwi.mul_(0.98)
+        hwi = hwi.numpy()
+        orb = oracle.awp_update(ost, oracle.stats(hwi, off)[:, 1], 0.0, 300, 8)
+    got = plan.read()
+    assert np.array_equal(got["counter"], ost.counter) and got["counter"].tolist() == [4, 4, 4]
+    assert np.array_equal(got["bytes"], orb)
+    np.testing.assert_allclose(got["stats"], oracle.stats(hwi, off), rtol=1e-10, atol=0.0)
+    assert np.array_equal(out.view(torch.int32).cpu().numpy(),
+                          oracle.unpack(oracle.pack(hwi, off, orb), off, orb).view(np.int32))
+    plan.close()
+
+
 def test_capture_refuses_a_plan_whose_last_batch_is_not_reduced_yet(adt):
     """An eager step may leave its final reduction to the next step; a step captured
     then would freeze that reduction into the graph.  The library refuses; after
