@@ -595,6 +595,72 @@ def test_carried_reduction_of_one_big_layer(adt, big):
     plan.close()
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_plan_random_configurations_against_the_oracle(adt, seed):
+    """Random layer sizes, groups, AWP parameters and output formats; the state is read,
+    flushed or left alone at random between steps, so that carried reductions, reductions
+    launched by a read and in-order steps with a redo pass follow each other in every
+    order.  Whenever the state is read it must equal the oracle's, and the stream and the
+    truncated weights of every step must equal the oracle's for that step."""
+    rng = np.random.default_rng(1000 + seed)
+    L = int(rng.integers(1, 12))
+    sizes = [int(x) for x in rng.choice([0, 1, 63, 1024, 4097, 30000, 262144, 700001], size=L)]
+    if sum(sizes) == 0:
+        sizes[0] = 5000
+    cuts = sorted(set(int(c) for c in rng.integers(0, L + 1, size=int(rng.integers(0, 4)))) | {0, L})
+    groups = cuts if rng.random() < 0.5 else list(range(L + 1))
+    grp = np.asarray(groups, np.int32)
+    G = grp.size - 1
+    interval = int(rng.choice([1, 2, 3, 7, 50]))
+    n_bits = int(rng.choice([3, 8, 8, 16]))
+    T = float(rng.choice([0.0, -0.005, 0.02]))
+    init = int(rng.choice([5, 8, 8, 16]))
+    out_dtype = [torch.float32, torch.float32, torch.bfloat16, torch.float16][int(rng.integers(0, 4))]
+    off = workloads.offsets_from_sizes(sizes)
+    N = int(off[-1])
+    hw = rng.standard_normal(N).astype(np.float32) * np.float32(0.05)
+    w = torch.from_numpy(hw).cuda()
+    steps = 14
+    packed = [torch.full((4 * N + 8,), 0xA5, dtype=torch.uint8, device="cuda") for _ in range(steps)]
+    outs = [torch.zeros(N, dtype=out_dtype, device="cuda") for _ in range(steps)]
+    plan = adt.AwpPlan(off, T, interval, n_bits, init_bits=np.full(G, init, np.int32), group_offsets=groups)
+    ost = oracle.AwpState(G, init)
+    history = []
+    for i in range(steps):
+        if i:
+            hw = hw * np.float32(rng.choice([0.9, 0.97, 1.0, 1.01, 1.1]))
+            w.copy_(torch.from_numpy(hw))
+        plan.step(w, packed[i], outs[i])
+        gb = oracle.awp_update(ost, oracle.group_norms(hw, off, grp), T, interval, n_bits)
+        orb = np.repeat(gb, np.diff(grp)).astype(np.uint8)
+        history.append((hw.copy(), orb))
+        action = rng.integers(0, 4)
+        if action == 0:
+            got = plan.read()
+            assert np.array_equal(got["bytes"], orb), (seed, i)
+            assert np.array_equal(got["bits"], ost.bits) and np.array_equal(got["counter"], ost.counter)
+            np.testing.assert_allclose(got["stats"], oracle.stats(hw, off), rtol=1e-10, atol=0.0)
+        elif action == 1:
+            plan.flush()
+        elif action == 2:
+            torch.cuda.synchronize()
+    got = plan.read()
+    assert np.array_equal(got["bits"], ost.bits) and np.array_equal(got["counter"], ost.counter)
+    for i, (hwi, orb) in enumerate(history):
+        exp = oracle.pack(hwi, off, orb)
+        hp = packed[i].cpu().numpy()
+        assert np.array_equal(hp[:exp.size], exp), (seed, i)
+        assert np.all(hp[4 * N:] == 0xA5)
+        if out_dtype == torch.float32:
+            assert np.array_equal(outs[i].view(torch.int32).cpu().numpy(),
+                                  oracle.unpack(exp, off, orb).view(np.int32)), (seed, i)
+        else:
+            fmt = "bf16" if out_dtype == torch.bfloat16 else "fp16"
+            assert np.array_equal(outs[i].view(torch.int16).cpu().numpy().view(np.uint16),
+                                  oracle.unpack16(exp, off, orb, fmt)), (seed, i)
+    plan.close()
+
+
 def test_capture_refuses_a_plan_whose_last_batch_is_not_reduced_yet(adt):
     """An eager step may leave its final reduction to the next step; a step captured
     then would freeze that reduction into the graph.  The library refuses; after
