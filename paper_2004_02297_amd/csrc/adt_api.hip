@@ -57,6 +57,8 @@ struct awp_plan {
     char *block = nullptr;          // one device allocation holding all of the below
     int64_t *elem_off = nullptr, *pack_off = nullptr, *packed_size = nullptr;
     uint32_t *tile_off = nullptr, *partial_absmax = nullptr;
+    uint32_t *tile_pivots = nullptr;        // first level of the kernels' tile search
+    int pivot_step = 1;
     uint8_t *rbytes = nullptr;
     int32_t *bits = nullptr, *counter = nullptr, *changed = nullptr, *steps_done = nullptr;
     // Leaving the redo launch out (see plan_step): what the fused kernel's first
@@ -724,9 +726,13 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     const size_t S = subs.size();
     pl->n_subs = (int)S;
 
-    // carve one allocation; 8-byte items first
+    // carve one allocation (hipMalloc aligns it to 256 bytes); the pivots need 64-byte
+    // alignment and go first, then the 8-byte items
     size_t o = 0;
     auto take = [&o](size_t bytes) { size_t at = o; o += align8(bytes); return at; };
+    const size_t o_piv = take(64);
+    uint32_t pivots[adt::kTilePivots];
+    pl->pivot_step = adt::tile_pivots(tile_off.data(), n_layers, pivots);
     const size_t o_elem = take(8 * L1), o_pack = take(8 * L1), o_psize = take(8);
     const size_t n_partials = (size_t)pl->n_tiles * adt::kWavesPerBlock;   // one per wave tile
     const size_t o_prev = take(8 * G), o_stats = take(24 * L), o_psum = take(2 * 8 * n_partials);
@@ -747,6 +753,7 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     pl->stats = (double *)(b + o_stats);
     pl->partial_sumsq = (double *)(b + o_psum);
     pl->tile_off = (uint32_t *)(b + o_tile);
+    pl->tile_pivots = (uint32_t *)(b + o_piv);
     pl->partial_absmax = (uint32_t *)(b + o_pmax);
     pl->bits = (int32_t *)(b + o_bits);
     pl->counter = (int32_t *)(b + o_cnt);
@@ -778,6 +785,7 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     if (e == hipSuccess) e = hipMemcpy(pl->pack_off, pack_off.data(), 8 * L1, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(pl->packed_size, &p, 8, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(pl->tile_off, tile_off.data(), 4 * L1, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(pl->tile_pivots, pivots, sizeof(pivots), hipMemcpyHostToDevice);
     if (e == hipSuccess && G) e = hipMemcpy(pl->bits, bits.data(), 4 * G, hipMemcpyHostToDevice);
     if (e == hipSuccess)
         e = hipMemcpy(pl->group_off, groups.data(), 4 * (G + 1), hipMemcpyHostToDevice);
@@ -927,6 +935,8 @@ int plan_step(awp_plan *plan, const float *weights, uint8_t *packed, int64_t pac
     a.elem_off = plan->elem_off;
     a.pack_off = plan->pack_off;
     a.tile_off = plan->tile_off;
+    a.tile_pivots = plan->tile_pivots;
+    a.pivot_step = plan->pivot_step;
     a.rbytes = plan->rbytes;
     a.partial_sumsq = plan->partial_sumsq + (size_t)set * n_partials;
     a.partial_absmax = plan->partial_absmax + (size_t)set * n_partials;

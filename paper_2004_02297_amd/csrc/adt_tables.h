@@ -120,7 +120,39 @@ __device__ __forceinline__ int table_byte(const uint8_t *table, int idx) {
     const uint32_t word = table_load((const uint32_t *)table, idx >> 2);
     return (int)((word >> (8 * (idx & 3))) & 0xFFu);
 }
+
+// Sixteen table entries with one scalar load (the table must be 64-byte
+// aligned).  A wave's life at the occupancy these kernels run at is a few
+// microseconds, and every dependent look-up before its first streaming load is
+// a round trip of that life: the first level of the tile search therefore reads
+// sixteen pivots at once and compares them in scalar registers.
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ u32x16 table_load16(const uint32_t *table) {
+    typedef const u32x16 __attribute__((address_space(4))) *ConstantPtr;
+    return *(ConstantPtr)table;
+}
+// pivots[i] = tile_off[min(i * step, n_layers)], i = 0..15 (see tile_pivots).
+// Returns the first layer of the range of `step` layers that holds `tile`.
+__device__ __forceinline__ int pivot_range(const uint32_t *pivots, int step, uint32_t tile) {
+    const u32x16 p = table_load16(pivots);
+    int c = 0;
+#pragma unroll
+    for (int i = 1; i < 16; ++i) c += p[i] <= tile ? 1 : 0;     // the pivots do not decrease
+    return c * step;
+}
 #endif
+
+// First level of the tile search: sixteen pivots out of tile_off (n_layers + 1
+// entries, non-decreasing), `step` layers apart; returns step.
+constexpr int kTilePivots = 16;
+inline int tile_pivots(const uint32_t *tile_off, int n_layers, uint32_t *pivots) {
+    const int step = n_layers <= kTilePivots ? 1 : (n_layers + kTilePivots - 1) / kTilePivots;
+    for (int i = 0; i < kTilePivots; ++i) {
+        const int64_t l = (int64_t)i * step;
+        pivots[i] = tile_off[l < n_layers ? l : n_layers];
+    }
+    return step;
+}
 
 // Layer l covers weights [elem_off[l], elem_off[l+1]), packed bytes
 // [pack_off[l], pack_off[l+1]) and tiles [tile_off[l], tile_off[l+1]).
@@ -248,6 +280,8 @@ struct FusedArgs {
     const int64_t *elem_off;
     const int64_t *pack_off;
     const uint32_t *tile_off;
+    const uint32_t *tile_pivots;    // kTilePivots entries, 64-byte aligned (see tile_pivots)
+    int pivot_step;
     const uint8_t *rbytes;
     double *partial_sumsq;      // one per wave tile: 4 * n_tiles entries (this batch's set)
     uint32_t *partial_absmax;

@@ -88,7 +88,10 @@ struct BlockTileRef {
 };
 
 __device__ __forceinline__ BlockTileRef find_block_tile(const FusedArgs &a, uint32_t tile) {
-    int lo = 0, hi = a.n_layers;            // largest lo with tile_off[lo] <= tile
+    // largest lo with tile_off[lo] <= tile: sixteen pivots at once, then a binary
+    // search inside the range they leave (no step at all up to sixteen layers)
+    int lo = pivot_range(a.tile_pivots, a.pivot_step, tile);
+    int hi = lo + a.pivot_step < a.n_layers ? lo + a.pivot_step : a.n_layers;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (table_load(a.tile_off, mid) <= tile) lo = mid; else hi = mid;
