@@ -696,7 +696,7 @@ int awp_plan_create_grouped(const int64_t *layer_offsets, int n_layers,
     pl->interval = interval;
     pl->n_bits = n_bits;
 
-    // sub-blocks of the final + rule kernel: first every layer's chunks in layer
+    // sub-blocks of the final reduction + rule: first every layer's chunks in layer
     // order, then one empty sub-block for every group that has no layer
     pl->final_slices = adt::final_slices_for((uint64_t)pl->n_tiles * adt::kWavesPerBlock);
     const uint32_t chunk = (uint32_t)pl->final_slices * adt::kFinalSlice;

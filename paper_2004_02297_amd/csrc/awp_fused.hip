@@ -138,12 +138,11 @@ __device__ __forceinline__ void fused_block_wave_tile(const FusedArgs &a, const 
 // kFinalSlice) to a sub-partial.  Phase 2: the sub-block that finishes last
 // among the sub-blocks of a group (a ticket counter per group, the one place in
 // the library where a block reads what another block of the same launch wrote)
-// adds up each of the group's layers
-// from its sub-partials, again in an order fixed by the indices alone, writes
-// the statistics and runs the rule for the group.  Which sub-block happens to be
-// last has no influence on any result, and neither has the launch the sub-blocks
-// ride in (a kernel of their own, or the head of the next batch's fused
-// kernel).
+// adds up each of the group's layers from its sub-partials, again in an order
+// fixed by the indices alone, writes the statistics and runs the rule for the
+// group.  Which sub-block happens to be last has no influence on any result,
+// and neither has the launch the sub-blocks ride in (a kernel of their own, or
+// the head of the next batch's fused kernel).
 struct FinalWork {          // what a sub-block's first wavefront knows before the reduction
     int g, layer, n_subs, l0, l1;
     uint32_t begin, end;
@@ -305,12 +304,15 @@ __global__ __launch_bounds__(kFinalBlock) void final_rule_kernel(const FinalRule
 
 // The first wavefront, before anything of the batch is reduced: clears
 // `changed`, hands the rule the "has a batch been seen" flag as it was before
-// this batch, and publishes to the host how far the interval counters had got
-// after the previous batch.  A byte count can only move in a batch that takes
-// some counter to INTERVAL (Algorithm 1), and a counter grows by at most one
-// per batch, so the host can tell from an old status word that the next batches
-// cannot change anything and leave the redo launch out (see plan_step).  All
-// 64 lanes must be active.
+// this batch, and publishes to the host how far the interval counters have got.
+// A byte count can only move in a batch that takes some counter to INTERVAL
+// (Algorithm 1), and a counter grows by at most one per batch, so the host can
+// tell from an old status word that the next batches cannot change anything
+// (see plan_step).  When the previous batch's rule is carried by this very
+// launch, a counter may be read before or after that rule advances it: either
+// value is at least what the batch before left, which is all the host assumes
+// (and no counter is reset in a launch that carries a rule: the host has shown
+// that none can reach INTERVAL).  All 64 lanes must be active.
 __device__ __forceinline__ void begin_batch(const FusedArgs &a, int lane) {
     uint32_t top = 0u;
     for (int g = lane; g < a.n_status_groups; g += kWave) {

@@ -1,6 +1,6 @@
 // Fixed-order reduction of per-tile statistics partials to per-layer statistics
 // (Section II of arXiv 2004.02297: the l2-norm of all weights of a layer), shared
-// by the final kernel of awp_layer_stats and by the plan's final + rule kernel.
+// by the final kernel of awp_layer_stats and by the plan's final reduction + rule.
 #pragma once
 
 #include <hip/hip_runtime.h>
