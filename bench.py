@@ -339,7 +339,9 @@ class Harness:
                 "host_and_gaps_ms_per_step": round(ms - t_k, 5),
                 "moved_gbps_whole_step": round(nbytes / ms / 1e6, 1),
                 "hbm_frac_whole_step": round(nbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                "roofline": self.roofline("fused_kernel", kernels["fused_kernel"], nbytes)}
+                "roofline": dict(self.roofline("fused_kernel", kernels["fused_kernel"], nbytes),
+                                 note="the launch also carries the previous batch's final reduction and "
+                                      "rule (a few dozen one-wave blocks at the head of the grid)")}
 
     def plan_graph_replay(self):
         """The plan's step captured once per buffer set and replayed round robin."""
