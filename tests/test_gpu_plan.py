@@ -661,6 +661,54 @@ def test_plan_random_configurations_against_the_oracle(adt, seed):
     plan.close()
 
 
+def test_carried_reduction_with_many_layers_and_changing_output_formats(adt):
+    """3000 small layers (thousands of carried sub-blocks, tile search beyond the
+    pivots, redo tables beyond LDS size) while nothing can move, the truncated
+    weights asked for as FP32, bfloat16, binary16 or not at all from step to step:
+    the state at the end and every step's stream against the oracle."""
+    rng = np.random.default_rng(74)
+    sizes = [int(x) for x in rng.integers(0, 6000, size=3000)]
+    off = workloads.offsets_from_sizes(sizes)
+    L, N = len(sizes), int(off[-1])
+    hw = rng.standard_normal(N).astype(np.float32) * np.float32(0.05)
+    w = torch.from_numpy(hw).cuda()
+    steps = 6
+    packed = [torch.zeros(4 * N, dtype=torch.uint8, device="cuda") for _ in range(steps)]
+    outs = [torch.zeros(N, dtype=torch.float32, device="cuda"),
+            torch.zeros(N, dtype=torch.bfloat16, device="cuda"),
+            None,
+            torch.zeros(N, dtype=torch.float16, device="cuda"),
+            torch.zeros(N, dtype=torch.float32, device="cuda"),
+            None]
+    plan = adt.AwpPlan(off, 0.0, 1000, 8, init_bits=np.full(L, 16, np.int32))
+    ost = oracle.AwpState(L, 16)
+    hist = []
+    for i in range(steps):
+        if i:
+            hw = hw * np.float32(0.97)
+            w.copy_(torch.from_numpy(hw))
+        plan.step(w, packed[i], outs[i])
+        orb = oracle.awp_update(ost, oracle.stats(hw, off)[:, 1], 0.0, 1000, 8)
+        hist.append((hw.copy(), orb))
+    got = plan.read()
+    assert np.array_equal(got["bits"], ost.bits) and np.array_equal(got["counter"], ost.counter)
+    assert got["counter"].max() == steps - 1
+    np.testing.assert_allclose(got["stats"], oracle.stats(hw, off), rtol=1e-10, atol=0.0)
+    for i, (hwi, orb) in enumerate(hist):
+        exp = oracle.pack(hwi, off, orb)
+        assert np.array_equal(packed[i][:exp.size].cpu().numpy(), exp), i
+        o = outs[i]
+        if o is None:
+            continue
+        if o.dtype == torch.float32:
+            assert np.array_equal(o.view(torch.int32).cpu().numpy(), oracle.unpack(exp, off, orb).view(np.int32)), i
+        else:
+            fmt = "bf16" if o.dtype == torch.bfloat16 else "fp16"
+            assert np.array_equal(o.view(torch.int16).cpu().numpy().view(np.uint16),
+                                  oracle.unpack16(exp, off, orb, fmt)), i
+    plan.close()
+
+
 def test_capture_refuses_a_plan_whose_last_batch_is_not_reduced_yet(adt):
     """An eager step may leave its final reduction to the next step; a step captured
     then would freeze that reduction into the graph.  The library refuses; after
