@@ -54,6 +54,25 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 TIMED_EVERY = 4          # launch timing is switched on for every 4th timed step
 ROTATE = 3               # distinct output buffer sets a timed loop cycles through
+# An idle GPU lowers its clocks and takes about 15 ms of work to raise them again
+# (measured here: after 2-10 s of idleness the first 25 steps run 7-10 % slow, the
+# next 40 steps 2-3 % slow, everything after that at one rate).  Every timed loop is
+# therefore preceded by at least this much untimed work of the same kind, on top of
+# the warm-up steps asked for; the steps it took are reported under "clock_settle".
+SETTLE_SECONDS = 0.1
+
+
+def settle_clocks(torch, work, seconds=SETTLE_SECONDS, first=0) -> int:
+    """Run work(i), i = first, first + 1, ..., untimed until `seconds` of wall time
+    have passed with the GPU busy throughout; returns the number of calls made."""
+    n = 0
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(16):
+            work(first + n)
+            n += 1
+        torch.cuda.synchronize()
+    return n
 
 WORKLOADS = {
     # name: (weight set, byte-count variant)
@@ -271,6 +290,7 @@ class Harness:
             if i % 32 == 31:
                 torch.cuda.synchronize()
         torch.cuda.synchronize()
+        self.settle_steps = settle_clocks(torch, step, first=prime + self.warmup)
         adt.adt_timing_enable(True, 8 * self.n_sampled)    # prepare event pairs up front
         adt.adt_timing_enable(False)
         adt.adt_timing_read()
@@ -335,6 +355,7 @@ class Harness:
                                                     "the next batch's fused kernel")
         t_k = sum(k["avg_ms"] for k in kernels.values())
         return {"value": round(4.0 * self.N / ms / 1e6, 2), "ms_per_step": round(ms, 5),
+                "settle_steps": self.settle_steps,
                 "kernels": kernels, "kernel_ms_per_step": round(t_k, 5),
                 "host_and_gaps_ms_per_step": round(ms - t_k, 5),
                 "moved_gbps_whole_step": round(nbytes / ms / 1e6, 1),
@@ -363,6 +384,7 @@ class Harness:
         for i in range(self.warmup):
             graphs[i % ROTATE].replay()
         torch.cuda.synchronize()
+        settle_clocks(torch, lambda i: graphs[i % ROTATE].replay())
         t0 = time.perf_counter()
         for i in range(self.steps):
             graphs[i % ROTATE].replay()
@@ -424,6 +446,7 @@ class Harness:
         for i in range(self.prime + 5):
             call(i)
         torch.cuda.synchronize()
+        settle_clocks(torch, call)
         adt.adt_timing_enable(True, launches)
         adt.adt_timing_read()
         for i in range(launches):
@@ -484,6 +507,7 @@ def run_trajectory(adt, torch, workloads, steps=200):
     plan = adt.AwpPlan(off, 0.0, 20, 8)
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
           for _ in range(steps)]
+    settle_clocks(torch, lambda i: w_out[i % ROTATE].copy_(w))    # plain copies: the plan's state stays untouched
     prev, per_step = None, []
     for s in range(steps):
         if s:
@@ -677,13 +701,19 @@ def main() -> int:
         "fused_pack_unpack": fused_pack_unpack,
     }
     for k, v in plan.items():
-        if k not in ("value", "ms_per_step", "roofline"):
+        if k not in ("value", "ms_per_step", "roofline", "settle_steps"):
             result[k] = v
     result["three_call_path"] = calls
     result["plan_bf16_out"] = {"value": plan16["value"], "ms_per_step": plan16["ms_per_step"],
                                "fused_kernel": plan16["kernels"]["fused_kernel"],
                                "algorithmic_bytes_per_launch": h.bytes_fused16}
     result["priming_steps"] = {"plan": 0, "three_call_path": h.prime, "fused_pack_unpack": h.prime}
+    result["clock_settle"] = {
+        "seconds": SETTLE_SECONDS, "untimed_plan_steps_before_the_headline_loop": plan["settle_steps"],
+        "note": "an idle GPU takes about 15 ms of work to raise its clocks again (first 25 steps "
+                "after idleness 7-10 % slow, the next 40 steps 2-3 % slow); every timed loop follows "
+                "--warmup steps plus this much untimed work of the same kind, so the figures are "
+                "those of a loop that keeps running"}
 
     head_ws, head_bits = h.ws, h.start_bits
     h.free()

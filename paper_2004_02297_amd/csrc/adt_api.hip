@@ -544,7 +544,7 @@ int awp_layer_stats(const float *weights, const int64_t *layer_offsets, int n_la
         if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(table)");
     }
     e = adt::launch_stats(a, f, n_tiles, inl,
-                          shape_of(adt::kKernelStatsPartial, adt::stats_shape()).extra_lds, hs);
+                          shape_of(adt::kKernelStatsPartial, adt::stats_shape(n_tiles)).extra_lds, hs);
     if (!inl) {
         if (hipEventRecord(slot->ev, hs) == hipSuccess) slot->pending = true;
         else (void)hipStreamSynchronize(hs);
@@ -610,7 +610,7 @@ int awp_layer_stats_noalloc(const float *weights, const int64_t *layer_offsets, 
     f.stats_out = stats_out;
     f.n_layers = n_layers;
     hipError_t e = adt::launch_stats(
-        a, f, n_tiles, true, shape_of(adt::kKernelStatsPartial, adt::stats_shape()).extra_lds,
+        a, f, n_tiles, true, shape_of(adt::kKernelStatsPartial, adt::stats_shape(n_tiles)).extra_lds,
         (hipStream_t)stream);
     if (e != hipSuccess) return fail_hip(e, "statistics launch");
     return ADT_OK;

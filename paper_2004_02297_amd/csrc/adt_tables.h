@@ -94,9 +94,13 @@ inline LaunchShape pack_shape(double, bool streaming) {
 inline LaunchShape unpack_shape(double bytes_per_weight, bool out16) {
     return LaunchShape{kUnpackWaves, out16 ? 2048u : bytes_per_weight <= 2.6 ? 6144u : 12288u};
 }
-// Statistics: 4-wave blocks of 8192 weights, 16 waves per compute unit (78 us for 138 M weights,
-// 79 us uncapped, 81 - 85 us with 12 or fewer waves).
-inline LaunchShape stats_shape() { return LaunchShape{4, 36864u}; }
+// Statistics: 4-wave blocks of 8192 weights, 16 waves per compute unit (77 us for 138 M weights,
+// 80 us uncapped or with any other cap; one- and two-wave blocks of 1024 - 4096 weights: 78 - 83 us
+// and a longer final kernel).  A grid of a few blocks per compute unit runs uncapped: with the cap
+// 3113 blocks (25 M weights) make just over three rounds of 1024 resident blocks, 15.4 us against 14.1.
+inline LaunchShape stats_shape(uint32_t n_tiles) {
+    return LaunchShape{4, n_tiles <= 4096u ? 0u : 36864u};
+}
 
 constexpr int kInlineLayers = 128;
 

@@ -66,19 +66,16 @@ __global__ __launch_bounds__(kBlock) void stats_partial_kernel(const StatsArgs a
     double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
     uint32_t mag = 0u;
     if (len == kStatsTile) {
+        u32x4 v[kStatsLoadsPerLane];        // all of a lane's loads are in flight together
 #pragma unroll
-        for (int it = 0; it < kStatsLoadsPerLane / 4; ++it) {
-            u32x4 v[4];
+        for (int j = 0; j < kStatsLoadsPerLane; ++j)
+            v[j] = __builtin_nontemporal_load((const u32x4_a4 *)(src + 4 * (j * kBlock + tid)));
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                v[j] = __builtin_nontemporal_load((const u32x4_a4 *)(src + 4 * ((it * 4 + j) * kBlock + tid)));
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                square_add(v[j].x, acc0, mag);
-                square_add(v[j].y, acc1, mag);
-                square_add(v[j].z, acc2, mag);
-                square_add(v[j].w, acc3, mag);
-            }
+        for (int j = 0; j < kStatsLoadsPerLane; ++j) {
+            square_add(v[j].x, acc0, mag);
+            square_add(v[j].y, acc1, mag);
+            square_add(v[j].z, acc2, mag);
+            square_add(v[j].w, acc3, mag);
         }
     } else {
         for (int i = 0; i < kStatsLoadsPerLane; ++i) {
