@@ -328,12 +328,16 @@ class Harness:
                 "unit": "GB/s", "frac": k["hbm_frac"], "algorithmic_bytes_per_launch": nbytes,
                 "traffic": recorded_traffic(traffic_key or kernel, self.workload)}
 
-    def plan_path(self, rotate=True, out16=False):
+    def plan_path(self, rotate=True, out16=False, no_out=False):
+        """no_out: statistics, rule and stream only (no truncated copy): the step of a
+        device that only sends the stream."""
         adt, torch = self.adt, self.torch
         plan = adt.AwpPlan(self.off, self.T, self.INTERVAL, self.N_BITS, init_bits=self.start_bits)
         outs = self.w_out
         if out16:
             outs = [torch.empty(self.N, dtype=torch.bfloat16, device="cuda") for _ in range(ROTATE)]
+        if no_out:
+            outs = [None] * ROTATE
         m = ROTATE if rotate else 1
         # the last batch's final reduction is launched by the read: inside the timed region
         ms, timing = self.timed_region(lambda i: plan.step(self.w, self.packed[i % m], outs[i % m]),
@@ -342,7 +346,7 @@ class Harness:
         assert np.array_equal(got["bytes"], self.rb), "AWP state drifted"
         assert got["packed_size"] == self.packed_bytes
         plan.close()
-        nbytes = self.bytes_fused16 if out16 else self.bytes_fused
+        nbytes = self.bytes_pack if no_out else self.bytes_fused16 if out16 else self.bytes_fused
         kernels = {"fused_kernel": self.kern(timing, ["fused_kernel"], nbytes),
                    "final_rule_kernel": self.kern(timing, ["final_rule_kernel"]),
                    "redo_kernel": self.kern(timing, ["redo_kernel"])}
@@ -662,6 +666,7 @@ def main() -> int:
     graph = h.plan_graph_replay()
     calls = h.three_calls()
     plan16 = h.plan_path(out16=True)
+    plan_send = h.plan_path(no_out=True)
     fused_pack_unpack = h.pack_unpack(max(10, min(args.steps, 50)))
     if args.calibrate_copy:
         h.w_out[0].copy_(h.w)
@@ -707,6 +712,11 @@ def main() -> int:
     result["plan_bf16_out"] = {"value": plan16["value"], "ms_per_step": plan16["ms_per_step"],
                                "fused_kernel": plan16["kernels"]["fused_kernel"],
                                "algorithmic_bytes_per_launch": h.bytes_fused16}
+    result["plan_stream_only"] = {"value": plan_send["value"], "ms_per_step": plan_send["ms_per_step"],
+                                  "fused_kernel": plan_send["kernels"]["fused_kernel"],
+                                  "algorithmic_bytes_per_launch": h.bytes_pack,
+                                  "note": "awp_adt_step without the truncated copy: statistics, rule and "
+                                          "stream in one launch, 4 + r bytes per weight"}
     result["priming_steps"] = {"plan": 0, "three_call_path": h.prime, "fused_pack_unpack": h.prime}
     result["clock_settle"] = {
         "seconds": SETTLE_SECONDS, "untimed_plan_steps_before_the_headline_loop": plan["settle_steps"],

@@ -80,7 +80,9 @@ inline LaunchShape fused_shape(double written_per_weight, int out_bytes) {
                               : written_per_weight <= 5.5 ? 10240u
                                                           : 12288u};
     if (out_bytes == 4) return LaunchShape{1, written_per_weight <= 6.5 ? 12288u : 14336u};
-    return LaunchShape{1, 4096u};       // statistics and stream only
+    // statistics and stream only (us at 1 / 2 / 3 / 4 bytes): 4 KB 108 / 126 / 150 / 172,
+    // 8 KB 113 / 129 / 149 / 169, 10 KB 122 / 137 / 152 / 168; no cap 118 / 131 / 155 / 177
+    return LaunchShape{1, written_per_weight <= 2.6 ? 4096u : written_per_weight <= 3.5 ? 8192u : 10240u};
 }
 inline LaunchShape pack_unpack_shape(double bytes_per_weight) {
     return LaunchShape{1, bytes_per_weight <= 2.6 ? 14336u : 16384u};
