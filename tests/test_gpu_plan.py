@@ -665,6 +665,58 @@ def test_plan_random_configurations_against_the_oracle(adt, seed):
     plan.close()
 
 
+def test_two_plans_on_two_streams_do_not_disturb_each_other(adt):
+    """Two plans with different layer sets and parameters step on streams of their
+    own, interleaved and without any wait in between; every step of each must equal
+    the oracle's.  Everything a plan's step touches belongs to that plan."""
+    rng = np.random.default_rng(77)
+    cfg = [dict(sizes=[30000, 5, 262144, 4097, 700001], T=0.0, interval=2, n_bits=8, init=8,
+                dtype=torch.float32),
+           dict(sizes=[1024, 500000, 63, 131072], T=-0.005, interval=50, n_bits=16, init=16,
+                dtype=torch.bfloat16)]
+    steps = 10
+    runs = []
+    for c in cfg:
+        off = workloads.offsets_from_sizes(c["sizes"])
+        N, L = int(off[-1]), len(c["sizes"])
+        hw = rng.standard_normal(N).astype(np.float32) * np.float32(0.05)
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            w = torch.from_numpy(hw).cuda()
+            packed = [torch.full((4 * N,), 0xA5, dtype=torch.uint8, device="cuda") for _ in range(steps)]
+            outs = [torch.zeros(N, dtype=c["dtype"], device="cuda") for _ in range(steps)]
+        runs.append(dict(c=c, off=off, N=N, L=L, hw=hw, w=w, packed=packed, outs=outs, stream=stream,
+                         plan=adt.AwpPlan(off, c["T"], c["interval"], c["n_bits"],
+                                          init_bits=np.full(L, c["init"], np.int32)),
+                         ost=oracle.AwpState(L, c["init"]), history=[]))
+    torch.cuda.synchronize()
+    for i in range(steps):
+        for r in runs:
+            c = r["c"]
+            if i:
+                r["hw"] = r["hw"] * np.float32(rng.choice([0.9, 0.97, 1.01, 1.1]))
+            with torch.cuda.stream(r["stream"]):
+                r["w"].copy_(torch.from_numpy(r["hw"]), non_blocking=False)
+                r["plan"].step(r["w"], r["packed"][i], r["outs"][i])
+            orb = oracle.awp_update(r["ost"], oracle.stats(r["hw"], r["off"])[:, 1], c["T"],
+                                    c["interval"], c["n_bits"])
+            r["history"].append((r["hw"].copy(), orb))
+    for r in runs:
+        got = r["plan"].read()
+        assert np.array_equal(got["bits"], r["ost"].bits)
+        assert np.array_equal(got["counter"], r["ost"].counter)
+        for i, (hwi, orb) in enumerate(r["history"]):
+            exp = oracle.pack(hwi, r["off"], orb)
+            assert np.array_equal(r["packed"][i][:exp.size].cpu().numpy(), exp), i
+            if r["c"]["dtype"] == torch.float32:
+                assert np.array_equal(r["outs"][i].view(torch.int32).cpu().numpy(),
+                                      oracle.unpack(exp, r["off"], orb).view(np.int32)), i
+            else:
+                assert np.array_equal(r["outs"][i].view(torch.int16).cpu().numpy().view(np.uint16),
+                                      oracle.unpack16(exp, r["off"], orb, "bf16")), i
+        r["plan"].close()
+
+
 def test_carried_reduction_with_many_layers_and_changing_output_formats(adt):
     """3000 small layers (thousands of carried sub-blocks, tile search beyond the
     pivots, redo tables beyond LDS size) while nothing can move, the truncated
